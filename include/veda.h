@@ -1,0 +1,152 @@
+/*
+ * veda.h -- C ABI of the MI355X (gfx950) tile-sparse attention path for video DiTs:
+ * head-aware 3D tiling -> statistics-aware tile scoring -> per-query-tile top-k ->
+ * block-sparse flash attention with scatter back to token order.
+ *
+ * Conventions (all entry points):
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *    ordinary host memory read during the call.  The library allocates device memory only
+ *    inside veda_plan_create (a few KB of per-head tables, freed by veda_plan_destroy).
+ *  - Every stage call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL
+ *    is the default stream) and returns without synchronising.
+ *  - Arguments are checked on the host before anything is launched; a failed check returns
+ *    an error code and launches nothing.  HIP launch failures map to VEDA_ERR_HIP.
+ *  - No atomics, no data-dependent scheduling of arithmetic: equal inputs give equal bytes.
+ *  - Tokens are the raster flattening n = (t*H + h)*W + w of a latent grid (T,H,W)
+ *    (Sec. 3.1).  A head's tile shape pi = (p_t,p_h,p_w) with p_t*p_h*p_w = B (Eq. 7)
+ *    partitions the grid, each axis padded up to a multiple of the tile extent.  Tile i and
+ *    slot l of a token are
+ *        i = ((t/p_t)*n_h + h/p_h)*n_w + w/p_w,   l = ((t%p_t)*p_h + h%p_h)*p_w + w%p_w
+ *    so temporal neighbours inside a tile are p_h*p_w slots apart (App. A.5).  Heads may
+ *    have different shapes, hence different tile counts N_T[h]; tiles of all heads are
+ *    concatenated head by head ("global tile index" g = tile_off[h] + i).
+ *  - Only B = 64, head_dim in {64,128}, dtype in {f32,bf16}, heads <= 128 are supported.
+ */
+#ifndef VEDA_H_
+#define VEDA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VEDA_OK = 0,
+    VEDA_ERR_INVALID_ARG = 1,  /* null pointer, inconsistent sizes, k out of range, ...   */
+    VEDA_ERR_UNSUPPORTED = 2,  /* a valid request outside what the kernels are built for   */
+    VEDA_ERR_WORKSPACE = 3,    /* workspace_bytes smaller than veda_plan_workspace_bytes() */
+    VEDA_ERR_HIP = 4           /* a HIP runtime call or kernel launch failed               */
+} veda_status;
+
+typedef enum { VEDA_F32 = 0, VEDA_BF16 = 1 } veda_dtype;
+typedef enum { VEDA_ACT_IDENTITY = 0, VEDA_ACT_RELU = 1 } veda_act;
+
+/* Order of the 64 x d elements inside one tile of a tiled tensor. */
+typedef enum {
+    VEDA_TOKEN_MAJOR = 0,   /* [slot][channel]  -- used for Q~ and K~                      */
+    VEDA_CHANNEL_MAJOR = 1  /* [channel][slot]  -- used for V~ (K-major operand of P*V)     */
+} veda_tile_order;
+
+typedef struct veda_plan veda_plan; /* opaque; owned by the library */
+
+/* One self-attention call of one layer (Sec. 3.1; Alg. 2 inputs). */
+typedef struct {
+    int32_t batch, heads, head_dim;
+    int32_t T, H, W;            /* latent grid; N = T*H*W tokens                            */
+    int32_t tile_tokens;        /* B; must be 64                                            */
+    const int32_t* tile_shape;  /* host, [heads][3] = (p_t,p_h,p_w), product == B (Eq. 7)   */
+    veda_dtype dtype;           /* element type of Q,K,V,O and of the tiled tensors         */
+} veda_problem;
+
+/* Element strides of a token-order tensor x[b][h][n][c]; the channel stride is 1.
+ * Each stride must be a multiple of 16 bytes and the base 16-byte aligned. */
+typedef struct { int64_t b, h, n; } veda_strides;
+
+/* Per-head projection phi of the score estimator (Eq. 5): y = W2^T act(W1^T z + b1) + b2,
+ * or, with hidden == 0, the single affine layer y = W1^T z + b1 (w2,b2 ignored).
+ * Device fp32 arrays, one block per head, row-major [in][out]:
+ *   w1 [heads][in_dim][hidden ? hidden : out_dim], b1 [heads][hidden ? hidden : out_dim],
+ *   w2 [heads][hidden][out_dim],                    b2 [heads][out_dim].                   */
+typedef struct {
+    int32_t in_dim;   /* must be 3*head_dim (Avg|Max|Min)          */
+    int32_t hidden;   /* 0 or 1..1024                               */
+    int32_t out_dim;  /* latent size d', 1..256, multiple of 4      */
+    veda_act act;
+    const float *w1, *b1, *w2, *b2;
+} veda_mlp;
+
+/* ---- plan: host-side geometry of a problem --------------------------------------------- */
+
+/* Validates the problem, derives each head's tile grid and offsets, uploads the per-head
+ * table to the current device.  *out is written only on VEDA_OK. */
+veda_status veda_plan_create(const veda_problem* problem, veda_plan** out);
+void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
+
+int32_t veda_plan_tiles(const veda_plan*, int32_t head);      /* N_T[h]; -1 on bad args        */
+int64_t veda_plan_tile_offset(const veda_plan*, int32_t head);/* tile_off[h] = sum_{h'<h} N_T  */
+int64_t veda_plan_score_offset(const veda_plan*, int32_t head);/* sum_{h'<h} N_T[h']^2          */
+int64_t veda_plan_total_tiles(const veda_plan*);              /* sum_h N_T[h]                  */
+int64_t veda_plan_score_elems(const veda_plan*);              /* sum_h N_T[h]^2 (per batch)    */
+/* Bytes of scratch veda_tile_score needs for the given projections (descriptors + latents). */
+size_t veda_plan_workspace_bytes(const veda_plan*, const veda_mlp* phi_q, const veda_mlp* phi_k);
+
+/* ---- stage 1: head-aware 3D tiling (Sec. 4.2; Alg. 1 "Tiling"; Alg. 2 "Tile") ----------- */
+/* x        device, token order, strides sx, plan dtype.
+ * x_tiled  device, [batch][total_tiles][64*head_dim] in `order`; padded slots are zero.
+ * valid_mask device u64 [total_tiles] (bit l set iff slot l holds a real token) and
+ * valid_cnt  device i32 [total_tiles] (its popcount); either may be NULL.  Both depend
+ * only on the geometry, not on x or the batch index. */
+veda_status veda_tile_layout(const veda_plan*, const void* x, veda_strides sx, veda_tile_order order,
+                             void* x_tiled, uint64_t* valid_mask, int32_t* valid_cnt, void* stream);
+
+/* ---- stage 2: statistics-aware tile scoring (Eq. 4, Eq. 5; Alg. 2) ---------------------- */
+/* q_tiled,k_tiled  device, VEDA_TOKEN_MAJOR tiled tensors from stage 1.
+ * scores   device fp32 [batch][score_elems]; head h occupies a dense row-major
+ *          N_T[h] x N_T[h] block at score_offset(h): S[i][j] = phi_q(z_q,i).phi_k(z_k,j)*scale,
+ *          z = [Avg|Max|Min] over the tile's real tokens, per channel.
+ * Arithmetic is fp32 with a fixed order (slot-ascending add chain for Avg; one fma chain per
+ * output in ascending input index, started from the bias, for phi; one fma chain from +0 in
+ * ascending latent index, then one multiply by `scale`, for the score), so the scores are
+ * reproducible to the bit on any conforming fp32 implementation.
+ * workspace device scratch of at least veda_plan_workspace_bytes(); contents undefined after. */
+veda_status veda_tile_score(const veda_plan*, const void* q_tiled, const void* k_tiled,
+                            const uint64_t* valid_mask, const veda_mlp* phi_q, const veda_mlp* phi_k,
+                            float scale, float* scores, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* ---- stage 3: per-query-tile top-k (Sec. 3.1 "exactly k per row"; Sec. 4.1; Alg. 2) ------ */
+/* scores      device, as written by stage 2.
+ * k_per_head  host i32 [heads], 1 <= k[h] <= N_T[h].
+ * row_ptr     device i32 [batch*total_tiles + 1]; row r = b*total_tiles + g.
+ * col_idx     device i32 [batch * sum_h N_T[h]*k[h]]; for each row the k[h] kept key tiles,
+ *             head-local indices in ascending order.
+ * A key tile is kept iff fewer than k[h] tiles of the row rank before it, where j ranks
+ * before j' if s_j > s_j', or s_j == s_j' and j < j' (NaN counts as -inf, -0 as +0). */
+veda_status veda_tile_select(const veda_plan*, const float* scores, const int32_t* k_per_head,
+                             int32_t* row_ptr, int32_t* col_idx, void* stream);
+
+/* ---- stage 4: block-sparse flash attention + un-tiling (Eq. 2; Sec. 4.3; Alg. 1 "UnTile") -- */
+/* q_tiled,k_tiled  VEDA_TOKEN_MAJOR; v_tiled VEDA_CHANNEL_MAJOR; valid_mask from stage 1.
+ * row_ptr/col_idx  CSR lists as written by stage 3 (any order within a row is accepted;
+ *                  every row needs at least one entry, indices in [0, N_T[h])).
+ * out      device, token order, strides so, plan dtype: for every real query token u of
+ *          query tile i, O[u] = softmax over the real tokens of the kept key tiles of
+ *          (q_u.k_v * softmax_scale) applied to V.  Padded query slots write nothing.
+ * lse      optional device fp32 [batch][heads][N]: natural-log sum of exp of the kept logits.
+ * bf16: Q K^T and P V run on bf16 MFMA with fp32 accumulation, softmax in fp32, P rounded
+ * to bf16 before P V.  f32: fp32 arithmetic throughout. */
+veda_status veda_sparse_attn_fwd(const veda_plan*, const void* q_tiled, const void* k_tiled,
+                                 const void* v_tiled, const uint64_t* valid_mask,
+                                 const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
+                                 void* out, veda_strides so, float* lse, void* stream);
+
+const char* veda_status_string(veda_status);
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* veda_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VEDA_H_ */

@@ -1,0 +1,127 @@
+// Stage 1 -- head-aware 3D tiling (Sec. 4.2: per-head pi = (p_t,p_h,p_w); Alg. 1 "Tiling";
+// Alg. 2 "Tile"): gathers the tokens of every tile into one contiguous 64 x d block, zero
+// fills padded slots and records which slots are real.  Pure byte movement, HBM bound:
+// one workgroup per (tile, batch) moves 64 rows with 16-byte accesses.
+#include "veda_internal.h"
+
+namespace veda {
+
+// out tile = [64][row_bytes]; each thread moves 16-byte chunks.
+__global__ __launch_bounds__(256) void layout_token_major_kernel(
+    const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
+    const char* __restrict__ x, int64_t sb, int64_t sh, int64_t sn, char* __restrict__ out,
+    int64_t total_tiles, int row_bytes, int T, int H, int W,
+    uint64_t* __restrict__ valid_mask, int32_t* __restrict__ valid_cnt) {
+    __shared__ int tok[kTile];
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int head = tile_head[g];
+    const HeadGeom hg = heads[head];
+    const int i = g - hg.tile_off;
+    if (threadIdx.x < kTile) {
+        const int n = slot_token(hg, i, threadIdx.x, T, H, W);
+        tok[threadIdx.x] = n;
+        const uint64_t m = __ballot(n >= 0);
+        if (threadIdx.x == 0 && b == 0) {
+            if (valid_mask) valid_mask[g] = m;
+            if (valid_cnt) valid_cnt[g] = __popcll(m);
+        }
+    }
+    __syncthreads();
+    const int cpr = row_bytes >> 4;  // 16-byte chunks per row
+    const char* xb = x + b * sb + head * sh;
+    char* ob = out + ((int64_t)b * total_tiles + g) * (int64_t)kTile * row_bytes;
+    for (int c = threadIdx.x; c < kTile * cpr; c += 256) {
+        const int l = c / cpr, ch = c - l * cpr;
+        const int n = tok[l];
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n >= 0) v = *reinterpret_cast<const uint4*>(xb + (int64_t)n * sn + ch * 16);
+        *reinterpret_cast<uint4*>(ob + (int64_t)c * 16) = v;
+    }
+}
+
+// out tile = [d][64] elements.  The tile is staged in LDS as [64][d] with one pad dword per
+// row so that the column gathers spread over the banks.
+template <typename E, int D>
+__global__ __launch_bounds__(256) void layout_channel_major_kernel(
+    const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
+    const char* __restrict__ x, int64_t sb, int64_t sh, int64_t sn, char* __restrict__ out,
+    int64_t total_tiles, int T, int H, int W,
+    uint64_t* __restrict__ valid_mask, int32_t* __restrict__ valid_cnt) {
+    constexpr int kRowBytes = D * (int)sizeof(E);
+    constexpr int kRowWords = kRowBytes / 4;
+    constexpr int kPitch = kRowWords + 1;   // dwords
+    constexpr int kCpr = kRowBytes / 16;
+    constexpr int kEpc = 16 / (int)sizeof(E);  // elements per 16-byte output chunk
+    __shared__ int tok[kTile];
+    __shared__ uint32_t stage[kTile * kPitch];
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int head = tile_head[g];
+    const HeadGeom hg = heads[head];
+    const int i = g - hg.tile_off;
+    if (threadIdx.x < kTile) {
+        const int n = slot_token(hg, i, threadIdx.x, T, H, W);
+        tok[threadIdx.x] = n;
+        const uint64_t m = __ballot(n >= 0);
+        if (threadIdx.x == 0 && b == 0) {
+            if (valid_mask) valid_mask[g] = m;
+            if (valid_cnt) valid_cnt[g] = __popcll(m);
+        }
+    }
+    __syncthreads();
+    const char* xb = x + b * sb + head * sh;
+    for (int c = threadIdx.x; c < kTile * kCpr; c += 256) {
+        const int l = c / kCpr, ch = c - l * kCpr;
+        const int n = tok[l];
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n >= 0) v = *reinterpret_cast<const uint4*>(xb + (int64_t)n * sn + ch * 16);
+        uint32_t* s = stage + l * kPitch + ch * 4;
+        s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
+    }
+    __syncthreads();
+    const E* se = reinterpret_cast<const E*>(stage);
+    constexpr int kPitchE = kPitch * 4 / (int)sizeof(E);
+    constexpr int kChunksPerChannel = kTile / kEpc;
+    char* ob = out + ((int64_t)b * total_tiles + g) * (int64_t)kTile * kRowBytes;
+    for (int oc = threadIdx.x; oc < D * kChunksPerChannel; oc += 256) {
+        const int ch = oc / kChunksPerChannel, l0 = (oc - ch * kChunksPerChannel) * kEpc;
+        E tmp[kEpc];
+#pragma unroll
+        for (int j = 0; j < kEpc; ++j) tmp[j] = se[(l0 + j) * kPitchE + ch];
+        *reinterpret_cast<uint4*>(ob + (int64_t)oc * 16) = *reinterpret_cast<const uint4*>(tmp);
+    }
+}
+
+}  // namespace veda
+
+extern "C" veda_status veda_tile_layout(const veda_plan* pl, const void* x, veda_strides sx,
+                                        veda_tile_order order, void* x_tiled, uint64_t* valid_mask,
+                                        int32_t* valid_cnt, void* stream) {
+    using namespace veda;
+    if (!pl || !x || !x_tiled) return VEDA_ERR_INVALID_ARG;
+    if (order != VEDA_TOKEN_MAJOR && order != VEDA_CHANNEL_MAJOR) return VEDA_ERR_INVALID_ARG;
+    const int es = pl->elem_size();
+    const int d = pl->prob.head_dim;
+    if (sx.n < d || sx.b < 0 || sx.h < 0) return VEDA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(x_tiled) || (sx.b * es) % 16 || (sx.h * es) % 16 || (sx.n * es) % 16)
+        return VEDA_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid((unsigned)pl->total_tiles, (unsigned)pl->prob.batch);
+    const int64_t sb = sx.b * es, sh = sx.h * es, sn = sx.n * es;
+    const int T = pl->prob.T, H = pl->prob.H, W = pl->prob.W;
+    if (order == VEDA_TOKEN_MAJOR) {
+        hipLaunchKernelGGL(layout_token_major_kernel, grid, dim3(256), 0, st, pl->d_heads, pl->d_tile_head,
+                           (const char*)x, sb, sh, sn, (char*)x_tiled, pl->total_tiles, d * es, T, H, W,
+                           valid_mask, valid_cnt);
+    } else {
+#define VEDA_LAUNCH_CM(E, D)                                                                           \
+    hipLaunchKernelGGL((layout_channel_major_kernel<E, D>), grid, dim3(256), 0, st, pl->d_heads,        \
+                       pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, pl->total_tiles, T, \
+                       H, W, valid_mask, valid_cnt)
+        if (es == 2 && d == 128) VEDA_LAUNCH_CM(uint16_t, 128);
+        else if (es == 2 && d == 64) VEDA_LAUNCH_CM(uint16_t, 64);
+        else if (es == 4 && d == 128) VEDA_LAUNCH_CM(uint32_t, 128);
+        else VEDA_LAUNCH_CM(uint32_t, 64);
+#undef VEDA_LAUNCH_CM
+    }
+    return launch_status("veda_tile_layout");
+}

@@ -1,0 +1,135 @@
+// Plan object: validates a problem, derives every head's ceil-padded tile grid (Sec. 3.1 tiles
+// of size B; Sec. 4.2 per-head shapes from Omega, Eq. 7) and uploads the per-head table.
+#include <new>
+
+#include "veda_internal.h"
+
+namespace veda {
+
+static thread_local std::string g_last_error;
+
+void set_last_error(const std::string& s) { g_last_error = s; }
+
+veda_status hip_fail(hipError_t e, const char* what) {
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return VEDA_ERR_HIP;
+}
+
+}  // namespace veda
+
+using veda::HeadGeom;
+
+extern "C" {
+
+const char* veda_status_string(veda_status s) {
+    switch (s) {
+        case VEDA_OK: return "ok";
+        case VEDA_ERR_INVALID_ARG: return "invalid argument";
+        case VEDA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case VEDA_ERR_WORKSPACE: return "workspace too small";
+        case VEDA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* veda_last_error(void) { return veda::g_last_error.c_str(); }
+
+veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
+    if (!p || !out || !p->tile_shape) return VEDA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->heads < 1 || p->T < 1 || p->H < 1 || p->W < 1) return VEDA_ERR_INVALID_ARG;
+    if (p->dtype != VEDA_F32 && p->dtype != VEDA_BF16) return VEDA_ERR_INVALID_ARG;
+    if (p->tile_tokens != veda::kTile) return VEDA_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128) return VEDA_ERR_UNSUPPORTED;
+    if (p->heads > veda::kMaxHeads) return VEDA_ERR_UNSUPPORTED;
+    if ((int64_t)p->T * p->H * p->W > (int64_t)1 << 30) return VEDA_ERR_UNSUPPORTED;
+    for (int h = 0; h < p->heads; ++h) {
+        const int32_t* s = p->tile_shape + 3 * h;
+        if (s[0] < 1 || s[1] < 1 || s[2] < 1) return VEDA_ERR_INVALID_ARG;
+        if ((int64_t)s[0] * s[1] * s[2] != p->tile_tokens) return VEDA_ERR_INVALID_ARG;
+    }
+
+    veda_plan* pl = new (std::nothrow) veda_plan();
+    if (!pl) return VEDA_ERR_INVALID_ARG;
+    pl->prob = *p;
+    pl->shapes.assign(p->tile_shape, p->tile_shape + 3 * p->heads);
+    pl->prob.tile_shape = pl->shapes.data();
+    pl->heads.resize(p->heads);
+    int64_t toff = 0, soff = 0, boff = 0;
+    for (int h = 0; h < p->heads; ++h) {
+        HeadGeom& g = pl->heads[h];
+        g.pt = pl->shapes[3 * h]; g.ph = pl->shapes[3 * h + 1]; g.pw = pl->shapes[3 * h + 2];
+        g.nt = (p->T + g.pt - 1) / g.pt;
+        g.nh = (p->H + g.ph - 1) / g.ph;
+        g.nw = (p->W + g.pw - 1) / g.pw;
+        const int64_t n = (int64_t)g.nt * g.nh * g.nw;
+        g.n_tiles = (int32_t)n;
+        g.tile_off = (int32_t)toff;
+        g.score_off = soff;
+        g.score_blk_dim = (int32_t)((n + 63) / 64);
+        g.score_blk_off = (int32_t)boff;
+        toff += n;
+        soff += n * n;
+        boff += (int64_t)g.score_blk_dim * g.score_blk_dim;
+    }
+    pl->total_tiles = toff;
+    pl->score_elems = soff;
+    pl->score_blocks = boff;
+    if (toff * p->batch >= ((int64_t)1 << 31) - 1 || boff >= ((int64_t)1 << 31)) {
+        delete pl;
+        return VEDA_ERR_UNSUPPORTED;
+    }
+
+    std::vector<uint8_t> tile_head((size_t)toff);
+    for (int h = 0; h < p->heads; ++h)
+        for (int32_t i = 0; i < pl->heads[h].n_tiles; ++i) tile_head[(size_t)pl->heads[h].tile_off + i] = (uint8_t)h;
+
+    hipError_t e = hipGetDevice(&pl->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_heads, pl->heads.data(), sizeof(HeadGeom) * p->heads, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_tile_head, tile_head.data(), tile_head.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        veda_status st = veda::hip_fail(e, "veda_plan_create");
+        veda_plan_destroy(pl);
+        return st;
+    }
+    *out = pl;
+    return VEDA_OK;
+}
+
+void veda_plan_destroy(veda_plan* pl) {
+    if (!pl) return;
+    if (pl->d_heads) (void)hipFree(pl->d_heads);
+    if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
+    delete pl;
+}
+
+int32_t veda_plan_tiles(const veda_plan* pl, int32_t head) {
+    if (!pl || head < 0 || head >= pl->prob.heads) return -1;
+    return pl->heads[head].n_tiles;
+}
+
+int64_t veda_plan_tile_offset(const veda_plan* pl, int32_t head) {
+    if (!pl || head < 0 || head >= pl->prob.heads) return -1;
+    return pl->heads[head].tile_off;
+}
+
+int64_t veda_plan_score_offset(const veda_plan* pl, int32_t head) {
+    if (!pl || head < 0 || head >= pl->prob.heads) return -1;
+    return pl->heads[head].score_off;
+}
+
+int64_t veda_plan_total_tiles(const veda_plan* pl) { return pl ? pl->total_tiles : -1; }
+
+int64_t veda_plan_score_elems(const veda_plan* pl) { return pl ? pl->score_elems : -1; }
+
+size_t veda_plan_workspace_bytes(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k) {
+    if (!pl || !phi_q || !phi_k) return 0;
+    const size_t rows = (size_t)pl->prob.batch * (size_t)pl->total_tiles;
+    const size_t per_row = (size_t)(2 * 3 * pl->prob.head_dim + phi_q->out_dim + phi_k->out_dim);
+    return ((rows * per_row * sizeof(float)) + 255) / 256 * 256;
+}
+
+}  // extern "C"

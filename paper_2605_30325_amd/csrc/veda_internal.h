@@ -1,0 +1,75 @@
+// Shared declarations of the library's translation units: the plan object, the per-head
+// geometry table the kernels read, and small host helpers.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "veda.h"
+
+namespace veda {
+
+constexpr int kTile = 64;        // B: tokens per tile
+constexpr int kMaxHeads = 128;   // per-call tables passed by value are sized for this
+
+// Per-head geometry, one entry per head, in device memory (plan->d_heads).
+struct HeadGeom {
+    int32_t pt, ph, pw;      // tile extents
+    int32_t nt, nh, nw;      // tile grid (ceil)
+    int32_t n_tiles;         // nt*nh*nw
+    int32_t tile_off;        // first global tile index of this head
+    int64_t score_off;       // first score element of this head (per batch)
+    int32_t score_blk_off;   // first 64x64 score block of this head
+    int32_t score_blk_dim;   // ceil(n_tiles / 64)
+};
+
+#if defined(__HIPCC__)
+// Token index of slot l of tile i of a head, or -1 for a padded slot.  Tiles and slots are
+// both raster order with time slowest (App. A.5: temporal neighbours p_h*p_w slots apart).
+__device__ inline int slot_token(const HeadGeom& g, int i, int l, int T, int H, int W) {
+    const int tw = i % g.nw, th = (i / g.nw) % g.nh, tt = i / (g.nw * g.nh);
+    const int lw = l % g.pw, lh = (l / g.pw) % g.ph, lt = l / (g.pw * g.ph);
+    const int t = tt * g.pt + lt, h = th * g.ph + lh, w = tw * g.pw + lw;
+    return (t < T && h < H && w < W) ? (t * H + h) * W + w : -1;
+}
+#endif
+
+}  // namespace veda
+
+struct veda_plan {
+    veda_problem prob;                  // tile_shape pointer is not kept valid; see shapes
+    std::vector<int32_t> shapes;        // [heads][3]
+    std::vector<veda::HeadGeom> heads;  // host copy
+    int64_t total_tiles = 0;
+    int64_t score_elems = 0;
+    int64_t score_blocks = 0;
+    int device = -1;
+    veda::HeadGeom* d_heads = nullptr;  // device [heads]
+    uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
+    int elem_size() const { return prob.dtype == VEDA_BF16 ? 2 : 4; }
+    int64_t tokens() const { return (int64_t)prob.T * prob.H * prob.W; }
+};
+
+namespace veda {
+
+void set_last_error(const std::string& s);
+veda_status hip_fail(hipError_t e, const char* what);
+
+#define VEDA_HIP_TRY(expr)                                              \
+    do {                                                                \
+        hipError_t e__ = (expr);                                        \
+        if (e__ != hipSuccess) return ::veda::hip_fail(e__, #expr);     \
+    } while (0)
+
+// After a kernel launch: map a launch error to VEDA_ERR_HIP without synchronising.
+inline veda_status launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? VEDA_OK : hip_fail(e, what);
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace veda

@@ -1,0 +1,259 @@
+"""ctypes binding of libveda.so: argument marshalling only.
+
+Every function below maps one-to-one onto the C entry point of the same name in
+include/veda.h and does nothing but turn torch tensors into pointers, sizes and the current
+HIP stream.  PyTorch provides device memory and streams; all arithmetic runs in the HIP
+kernels.  There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libveda.so"
+
+VEDA_OK, VEDA_ERR_INVALID_ARG, VEDA_ERR_UNSUPPORTED, VEDA_ERR_WORKSPACE, VEDA_ERR_HIP = range(5)
+VEDA_F32, VEDA_BF16 = 0, 1
+VEDA_ACT_IDENTITY, VEDA_ACT_RELU = 0, 1
+VEDA_TOKEN_MAJOR, VEDA_CHANNEL_MAJOR = 0, 1
+
+EXPORTS = (
+    "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
+    "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
+    "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_select",
+    "veda_sparse_attn_fwd", "veda_status_string", "veda_last_error",
+)
+
+
+class VedaError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: status {status}" + (f" ({detail})" if detail else ""))
+
+
+class veda_problem(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
+                ("T", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("tile_tokens", C.c_int32),
+                ("tile_shape", C.POINTER(C.c_int32)), ("dtype", C.c_int)]
+
+
+class veda_strides(C.Structure):
+    _fields_ = [("b", C.c_int64), ("h", C.c_int64), ("n", C.c_int64)]
+
+
+class veda_mlp(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32), ("act", C.c_int),
+                ("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Load libveda.so (built in-tree by paper_2605_30325_amd.build).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2605_30325_amd.build`")
+    L = C.CDLL(str(LIB_PATH))
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.veda_plan_create.argtypes = [C.POINTER(veda_problem), C.POINTER(vp)]
+    L.veda_plan_create.restype = C.c_int
+    L.veda_plan_destroy.argtypes = [vp]
+    L.veda_plan_destroy.restype = None
+    L.veda_plan_tiles.argtypes = [vp, i32]
+    L.veda_plan_tiles.restype = i32
+    for name in ("veda_plan_tile_offset", "veda_plan_score_offset"):
+        getattr(L, name).argtypes = [vp, i32]
+        getattr(L, name).restype = i64
+    for name in ("veda_plan_total_tiles", "veda_plan_score_elems"):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = i64
+    L.veda_plan_workspace_bytes.argtypes = [vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp)]
+    L.veda_plan_workspace_bytes.restype = C.c_size_t
+    L.veda_tile_layout.argtypes = [vp, vp, veda_strides, C.c_int, vp, vp, vp, vp]
+    L.veda_tile_layout.restype = C.c_int
+    L.veda_tile_score.argtypes = [vp, vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
+                                  vp, vp, C.c_size_t, vp]
+    L.veda_tile_score.restype = C.c_int
+    L.veda_tile_select.argtypes = [vp, vp, C.POINTER(i32), vp, vp, vp]
+    L.veda_tile_select.restype = C.c_int
+    L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
+    L.veda_sparse_attn_fwd.restype = C.c_int
+    L.veda_status_string.argtypes = [C.c_int]
+    L.veda_status_string.restype = C.c_char_p
+    L.veda_last_error.argtypes = []
+    L.veda_last_error.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str):
+    if status != VEDA_OK:
+        L = load()
+        detail = L.veda_status_string(status).decode()
+        if status == VEDA_ERR_HIP:
+            detail += ": " + L.veda_last_error().decode()
+        raise VedaError(status, where, detail)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _strides(t: torch.Tensor) -> veda_strides:
+    assert t.dim() == 4 and t.stride(3) == 1, "expected [batch, heads, N, d] with unit channel stride"
+    return veda_strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return VEDA_F32
+    if dt == torch.bfloat16:
+        return VEDA_BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+class Mlp:
+    """Device-resident projection weights as the veda_mlp struct expects them."""
+
+    def __init__(self, w1, b1, w2=None, b2=None, relu: bool = True, device="cuda"):
+        def dev(a):
+            return None if a is None else torch.as_tensor(np.ascontiguousarray(a, np.float32)).to(device).contiguous()
+        self.w1, self.b1, self.w2, self.b2 = dev(w1), dev(b1), dev(w2), dev(b2)
+        self.in_dim = int(self.w1.shape[1])
+        self.hidden = 0 if self.w2 is None else int(self.w1.shape[2])
+        self.out_dim = int(self.w1.shape[2] if self.w2 is None else self.w2.shape[2])
+        self.act = VEDA_ACT_RELU if relu else VEDA_ACT_IDENTITY
+
+    def struct(self) -> veda_mlp:
+        return veda_mlp(self.in_dim, self.hidden, self.out_dim, self.act,
+                        _ptr(self.w1), _ptr(self.b1), _ptr(self.w2), _ptr(self.b2))
+
+
+class Plan:
+    """veda_plan handle plus the sizes callers need to allocate buffers."""
+
+    def __init__(self, batch: int, heads: int, head_dim: int, grid: Sequence[int],
+                 tile_shape: np.ndarray, dtype: torch.dtype, tile_tokens: int = 64):
+        L = load()
+        self._shape = np.ascontiguousarray(tile_shape, np.int32).reshape(-1)
+        if self._shape.size != 3 * heads:
+            raise VedaError(VEDA_ERR_INVALID_ARG, "Plan", "tile_shape must be [heads, 3]")
+        prob = veda_problem(batch, heads, head_dim, int(grid[0]), int(grid[1]), int(grid[2]), tile_tokens,
+                            self._shape.ctypes.data_as(C.POINTER(C.c_int32)), _dtype_code(dtype))
+        h = C.c_void_p()
+        self.handle = None
+        _check(L.veda_plan_create(C.byref(prob), C.byref(h)), "veda_plan_create")
+        self.handle = h
+        self.batch, self.heads, self.head_dim, self.grid, self.dtype = batch, heads, head_dim, tuple(grid), dtype
+        self.tokens = int(grid[0]) * int(grid[1]) * int(grid[2])
+        self.tiles = [int(L.veda_plan_tiles(h, i)) for i in range(heads)]
+        self.tile_offset = [int(L.veda_plan_tile_offset(h, i)) for i in range(heads)]
+        self.score_offset = [int(L.veda_plan_score_offset(h, i)) for i in range(heads)]
+        self.total_tiles = int(L.veda_plan_total_tiles(h))
+        self.score_elems = int(L.veda_plan_score_elems(h))
+
+    def workspace_bytes(self, phi_q: Mlp, phi_k: Mlp) -> int:
+        return int(load().veda_plan_workspace_bytes(self.handle, C.byref(phi_q.struct()), C.byref(phi_k.struct())))
+
+    def close(self):
+        if self.handle is not None:
+            load().veda_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def veda_tile_layout(plan: Plan, x: torch.Tensor, order: int = VEDA_TOKEN_MAJOR,
+                     x_tiled: Optional[torch.Tensor] = None, valid_mask: Optional[torch.Tensor] = None,
+                     valid_cnt: Optional[torch.Tensor] = None, want_mask: bool = True):
+    """Stage 1.  Returns (x_tiled [batch, total_tiles, 64*d], valid_mask i64-as-u64, valid_cnt i32)."""
+    dev = x.device
+    if x_tiled is None:
+        x_tiled = torch.empty((plan.batch, plan.total_tiles, 64 * plan.head_dim), dtype=x.dtype, device=dev)
+    if want_mask and valid_mask is None:
+        valid_mask = torch.empty(plan.total_tiles, dtype=torch.int64, device=dev)
+    if want_mask and valid_cnt is None:
+        valid_cnt = torch.empty(plan.total_tiles, dtype=torch.int32, device=dev)
+    _check(load().veda_tile_layout(plan.handle, _ptr(x), _strides(x), order, _ptr(x_tiled), _ptr(valid_mask),
+                                   _ptr(valid_cnt), _stream()), "veda_tile_layout")
+    return x_tiled, valid_mask, valid_cnt
+
+
+def veda_tile_score(plan: Plan, q_tiled, k_tiled, valid_mask, phi_q: Mlp, phi_k: Mlp, scale: float,
+                    scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Stage 2.  Returns (scores fp32 [batch, score_elems], workspace)."""
+    dev = q_tiled.device
+    if scores is None:
+        scores = torch.empty((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
+    need = plan.workspace_bytes(phi_q, phi_k)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    sq, sk = phi_q.struct(), phi_k.struct()
+    _check(load().veda_tile_score(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(valid_mask), C.byref(sq),
+                                  C.byref(sk), C.c_float(scale), _ptr(scores), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream()), "veda_tile_score")
+    return scores, workspace
+
+
+def veda_tile_select(plan: Plan, scores, k_per_head: Sequence[int], row_ptr: Optional[torch.Tensor] = None,
+                     col_idx: Optional[torch.Tensor] = None):
+    """Stage 3.  Returns (row_ptr i32 [batch*total_tiles+1], col_idx i32 [batch*nnz])."""
+    k = np.ascontiguousarray(k_per_head, np.int32)
+    if k.size != plan.heads:
+        raise VedaError(VEDA_ERR_INVALID_ARG, "veda_tile_select", "k_per_head must have one entry per head")
+    nnz = int(sum(int(n) * int(kk) for n, kk in zip(plan.tiles, k)))
+    dev = scores.device
+    if row_ptr is None:
+        row_ptr = torch.empty(plan.batch * plan.total_tiles + 1, dtype=torch.int32, device=dev)
+    if col_idx is None:
+        col_idx = torch.empty(max(1, plan.batch * max(nnz, 0)), dtype=torch.int32, device=dev)
+    _check(load().veda_tile_select(plan.handle, _ptr(scores), k.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   _ptr(row_ptr), _ptr(col_idx), _stream()), "veda_tile_select")
+    return row_ptr, col_idx
+
+
+def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_ptr, col_idx,
+                         softmax_scale: float, out: Optional[torch.Tensor] = None,
+                         lse: Optional[torch.Tensor] = None, want_lse: bool = False):
+    """Stage 4.  Returns (out [batch, heads, N, d] in token order, lse or None)."""
+    dev = q_tiled.device
+    if out is None:
+        out = torch.empty((plan.batch, plan.heads, plan.tokens, plan.head_dim), dtype=plan.dtype, device=dev)
+    if want_lse and lse is None:
+        lse = torch.empty((plan.batch, plan.heads, plan.tokens), dtype=torch.float32, device=dev)
+    _check(load().veda_sparse_attn_fwd(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(v_tiled),
+                                       _ptr(valid_mask), _ptr(row_ptr), _ptr(col_idx), C.c_float(softmax_scale),
+                                       _ptr(out), _strides(out), _ptr(lse), _stream()), "veda_sparse_attn_fwd")
+    return out, lse
+
+
+def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,
+                   softmax_scale: float, buffers: Optional[dict] = None):
+    """The whole path in call order: layout x3 -> score -> select -> sparse attention.
+    `buffers` (optional dict) is filled on the first call and reused afterwards so that a
+    steady-state step allocates nothing."""
+    bufs = {} if buffers is None else buffers
+    qt, vm, vc = veda_tile_layout(plan, q, VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
+    kt, _, _ = veda_tile_layout(plan, k, VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
+    vt, _, _ = veda_tile_layout(plan, v, VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
+    s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+    rp, ci = veda_tile_select(plan, s, k_per_head, bufs.get("rp"), bufs.get("ci"))
+    out, _ = veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
+    bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)
+    return out, bufs

@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tile lists, masks, statistics and scores must match bit for bit; attention
+outputs within the stated tolerances."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as vo
+from paper_2605_30325_amd import veda
+from paper_2605_30325_amd import workloads as wlm
+from tests import harness as hz
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _full_check(wl, **kw):
+    _say(f"[parity] {wl.name}: grid {wl.grid} heads {wl.heads} d {wl.head_dim} {wl.dtype}")
+    run = hz.run_gpu_path(wl, **kw)
+    assert torch.isfinite(run.out.float()).all(), "a real token was left unwritten or is not finite"
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            st = hz.check_head(run, h, batch=b)
+            _say(f"[parity] {wl.name} b{b} h{h} {tuple(run.shapes[h])}: {st}")
+    return run
+
+
+def test_tiny_config_everything():
+    _full_check(wlm.WORKLOADS["tiny"])
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_small_ragged_grids_all_shapes(dtype, d):
+    # 6 heads cover the three tile shapes; every axis has a ragged tail for some shape
+    wl = wlm.custom_workload(f"ragged_{dtype}_{d}", 6, d, dtype, (9, 10, 14), True, (25, 100), seed=11,
+                             latent_dim=64 if d == 128 else 32)
+    run = _full_check(wl)
+    assert len({tuple(s) for s in run.shapes}) == 3
+
+
+def test_batch_two_and_strided_input():
+    wl = wlm.custom_workload("batch2", 3, 128, "bf16", (5, 8, 12), True, (30, 100), seed=12, batch=2)
+    _full_check(wl)
+    # [batch, N, heads, d] storage viewed as [batch, heads, N, d]: strides handed to the library
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, _, _ = wlm.make_qkv(wl, dev)
+    q_bnhd = q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not q_bnhd.is_contiguous()
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    a, _, _ = veda.veda_tile_layout(plan, q)
+    b, _, _ = veda.veda_tile_layout(plan, q_bnhd)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_zero_sparsity_equals_dense_attention_on_gpu():
+    wl = wlm.custom_workload("dense_identity", 3, 128, "bf16", (6, 9, 11), True, (1, 1), seed=13)
+    run = hz.run_gpu_path(wl)
+    assert list(run.k_per_head) == run.plan.tiles
+    for h in range(wl.heads):
+        qf, kf, vf = (hz.to_f32_numpy(t[0, h]) for t in (run.q, run.k, run.v))
+        ref = vo.dense_attention(qf, kf, vf, run.softmax_scale, np.arange(wl.tokens))
+        err = np.abs(hz.to_f32_numpy(run.out[0, h]).astype(np.float64) - ref)
+        _say(f"[dense-identity] head {h} {tuple(run.shapes[h])}: max {err.max():.3e} mean {err.mean():.3e}")
+        assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS
+
+
+def test_row_stochastic_weights_on_gpu():
+    # V == 1 everywhere: any convex combination of value rows is exactly 1 (bf16 can hold it)
+    wl = wlm.custom_workload("ones", 3, 128, "bf16", (6, 9, 11), True, (40, 100), seed=14)
+    run = hz.run_gpu_path(wl)
+    vt, _, _ = veda.veda_tile_layout(run.plan, torch.ones_like(run.v), veda.VEDA_CHANNEL_MAJOR, want_mask=False)
+    out, _ = veda.veda_sparse_attn_fwd(run.plan, run.bufs["qt"], run.bufs["kt"], vt, run.bufs["vm"],
+                                       run.bufs["rp"], run.bufs["ci"], run.softmax_scale)
+    torch.cuda.synchronize()
+    assert (out.float() - 1.0).abs().max().item() <= 2 ** -7
+
+
+def test_select_on_constructed_ties_and_special_values():
+    wl = wlm.custom_workload("ties", 2, 64, "f32", (4, 8, 40), False, (1, 4), seed=15, latent_dim=32)
+    shapes = wlm.tile_shapes(wl)
+    plan = veda.Plan(1, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    nt = plan.tiles[0]
+    rng = np.random.default_rng(15)
+    s = rng.integers(-2, 3, size=(wl.heads, nt, nt)).astype(np.float32)     # five levels: many ties
+    s[0, 0, :5] = [np.nan, -0.0, 0.0, np.inf, -np.inf]
+    s[1, 1, :] = 1.0                                                          # a fully tied row
+    for k in (1, 3, nt // 2, nt):
+        rp, ci = veda.veda_tile_select(plan, torch.as_tensor(s).reshape(1, -1).cuda(), [k] * wl.heads)
+        torch.cuda.synchronize()
+        got = ci.cpu().numpy().reshape(wl.heads, nt, k)
+        for h in range(wl.heads):
+            assert np.array_equal(got[h], vo.select(s[h], k)), (h, k)
+        assert np.array_equal(rp.cpu().numpy(), np.arange(wl.heads * nt + 1) * k)
+
+
+def test_select_long_rows_use_every_instantiation():
+    # row lengths that land in the 4-, 16-, 32-, 64-item and the memory-resident kernels
+    for grid in [(1, 8, 64), (32, 32, 64), (64, 32, 64), (128, 32, 64), (136, 32, 64)]:
+        shapes = np.asarray([[1, 8, 8]], np.int32)
+        plan = veda.Plan(1, 1, 64, grid, shapes, torch.float32)
+        nt = plan.tiles[0]
+        rows = min(nt, 48)
+        s = np.random.default_rng(nt).standard_normal((nt, nt)).astype(np.float32)
+        s[rows:] = 0.0
+        k = max(1, nt // 20)
+        rp, ci = veda.veda_tile_select(plan, torch.as_tensor(s).reshape(1, -1).cuda(), [k])
+        torch.cuda.synchronize()
+        got = ci.cpu().numpy().reshape(nt, k)
+        assert np.array_equal(got[:rows], vo.select(s[:rows], k)), grid
+        assert np.array_equal(got[rows:], np.tile(np.arange(k), (nt - rows, 1))), grid
+
+
+def test_gpu_argument_errors_launch_nothing():
+    wl = wlm.WORKLOADS["tiny"]
+    run = hz.run_gpu_path(wl, want_lse=False)
+    plan = run.plan
+    with pytest.raises(veda.VedaError) as e:
+        veda.veda_tile_select(plan, run.bufs["s"], [0, 2])
+    assert e.value.status == veda.VEDA_ERR_INVALID_ARG
+    with pytest.raises(veda.VedaError) as e:
+        veda.veda_tile_select(plan, run.bufs["s"], [2, plan.tiles[1] + 1])
+    assert e.value.status == veda.VEDA_ERR_INVALID_ARG
+    pq = veda.Mlp(run.phi_q.w1, run.phi_q.b1, run.phi_q.w2, run.phi_q.b2)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(veda.VedaError) as e:
+        veda.veda_tile_score(plan, run.bufs["qt"], run.bufs["kt"], run.bufs["vm"], pq, pq, 0.125, workspace=small)
+    assert e.value.status == veda.VEDA_ERR_WORKSPACE
+    with pytest.raises(veda.VedaError) as e:
+        veda.veda_sparse_attn_fwd(plan, run.bufs["qt"], run.bufs["kt"], run.bufs["vt"], run.bufs["vm"],
+                                  run.bufs["rp"], run.bufs["ci"], float("nan"))
+    assert e.value.status == veda.VEDA_ERR_INVALID_ARG
+
+
+def test_outputs_are_deterministic():
+    wl = wlm.custom_workload("determinism", 3, 128, "bf16", (6, 9, 11), True, (30, 100), seed=16)
+    a, b = hz.run_gpu_path(wl), hz.run_gpu_path(wl)
+    assert torch.equal(a.bufs["ci"], b.bufs["ci"]) and torch.equal(a.bufs["s"], b.bufs["s"])
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+
+
+def test_wan1p3b_480p_sampled():
+    wl = wlm.WORKLOADS["wan1p3b_480p"]
+    _say(f"[parity] {wl.name}")
+    run = hz.run_gpu_path(wl)
+    assert torch.isfinite(run.out.float()).all()
+    for h in (0, 7):
+        _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=12)}")
+
+
+@pytest.mark.parametrize("name", ["wan14b_480p", "wan14b_720p", "waver12b_720p_241f"])
+def test_large_configs_sampled(name):
+    """Full-size launch configuration; oracle on one head per tile shape and a seeded sample of
+    query tiles (first and last tile always included)."""
+    wl = wlm.WORKLOADS[name]
+    _say(f"[parity] {wl.name}: generating inputs")
+    run = hz.run_gpu_path(wl, want_lse=False)
+    for h in hz.heads_by_shape(run):
+        _say(f"[parity] {wl.name} head {h} {tuple(run.shapes[h])}: checking")
+        _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=6)}")
+    # every real token of every head was written (the output buffer starts as NaN)
+    for h in range(wl.heads):
+        assert torch.isfinite(run.out[0, h].float()).all(), h
