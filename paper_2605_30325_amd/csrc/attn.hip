@@ -30,7 +30,7 @@ namespace veda {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -113,24 +113,26 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         const int vrow = cid >> 3, vch = cid & 7;
         v_dst[j] = kKBytes + vrow * 128 + ((vch ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
     }
-    uint4 kreg[kLoads], vreg[kLoads];
-    auto fetch = [&](int j_tile) {
-        const char* ks = kt + (int64_t)j_tile * kKBytes + tid * 16;
-        const char* vs = vt + (int64_t)j_tile * kVBytes + tid * 16;
-#pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            kreg[j] = *reinterpret_cast<const uint4*>(ks + 4096 * j);
-            vreg[j] = *reinterpret_cast<const uint4*>(vs + 4096 * j);
-        }
-    };
-    auto stash = [&](int stage) {
-        char* base = smem + stage * kStage;
-#pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            *reinterpret_cast<uint4*>(base + k_dst[j]) = kreg[j];
-            *reinterpret_cast<uint4*>(base + v_dst[j]) = vreg[j];
-        }
-    };
+    // Staging registers of the tile in flight (plain unrolled code: the arrays must stay in
+    // VGPRs, so no lambdas or dynamic indexing touch them).
+    u32x4 kreg[kLoads], vreg[kLoads];
+#define VEDA_FETCH(j_tile)                                                            \
+    do {                                                                              \
+        const char* ks_ = kt + (int64_t)(j_tile) * kKBytes + tid * 16;                \
+        const char* vs_ = vt + (int64_t)(j_tile) * kVBytes + tid * 16;                \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j) {                          \
+            kreg[j] = *reinterpret_cast<const u32x4*>(ks_ + 4096 * j);                \
+            vreg[j] = *reinterpret_cast<const u32x4*>(vs_ + 4096 * j);                \
+        }                                                                             \
+    } while (0)
+#define VEDA_STASH(stage_)                                                            \
+    do {                                                                              \
+        char* base_ = smem + (stage_) * kStage;                                       \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j) {                          \
+            *reinterpret_cast<u32x4*>(base_ + k_dst[j]) = kreg[j];                    \
+            *reinterpret_cast<u32x4*>(base_ + v_dst[j]) = vreg[j];                    \
+        }                                                                             \
+    } while (0)
 
     // operand read offsets inside a stage
     const int k_row_off = (32 * c + rho(lq)) * kRowB;
@@ -153,8 +155,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
     int j_cur = nsel > 0 ? cols[0] : 0;
     uint64_t vm_cur = nsel > 0 ? vmask[j_cur] : 0ull;
     if (nsel > 0) {
-        fetch(j_cur);
-        stash(0);
+        VEDA_FETCH(j_cur);
+        VEDA_STASH(0);
     }
     __syncthreads();
 
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         if (more) {
             j_next = cols[it + 1];
             vm_next = vmask[j_next];
-            fetch(j_next);
+            VEDA_FETCH(j_next);
         }
         const char* sb = smem + stage * kStage;
 
@@ -224,12 +226,14 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
                 o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[nb], 0, 0, 0);
             }
         }
-        if (more) stash(stage ^ 1);
+        if (more) VEDA_STASH(stage ^ 1);
         j_cur = j_next;
         vm_cur = vm_next;
         __syncthreads();
     }
 
+#undef VEDA_FETCH
+#undef VEDA_STASH
     // ---- merge the two key halves, normalise, transpose through LDS, scatter to tokens ----
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     float* xo = reinterpret_cast<float*>(smem) + r * (32 * D + 64);  // [D][32] + m[32] + l[32]
