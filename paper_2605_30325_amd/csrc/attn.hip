@@ -17,10 +17,10 @@
 // makes those eight keys per lane-half contiguous, so the V^T operand is one 16-byte LDS
 // read from the channel-major V tile.
 //
-// K and V^T tiles are double buffered in LDS (2 x 32 KB for d = 128): the next tile is
-// fetched from global memory into registers while the current one is multiplied, then
-// stored to the other buffer.  16-byte chunks are XOR-swizzled inside each LDS row so the
-// per-lane row-strided operand reads do not pile onto the same banks.
+// K and V^T tiles are double buffered in LDS (2 x 32 KB for d = 128) and filled by direct
+// global->LDS loads, K running one step ahead of V: while the vector ALUs do the softmax of
+// step i the matrix cores already form S of step i+1.  16-byte chunks are XOR-swizzled inside
+// each LDS row so the per-lane row-strided operand reads do not pile onto the same banks.
 //
 // fp32 kernel: plain fp32 VALU arithmetic, one workgroup per query tile (small problems and
 // the 1e-4 accuracy bar; not a throughput path).
@@ -30,7 +30,6 @@ namespace veda {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -38,6 +37,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct AttnArgs {
     const HeadGeom* heads;
     const uint8_t* tile_head;
+    const int32_t* xcd_cum;
     const char* q;
     const char* k;
     const char* v;
@@ -53,18 +53,40 @@ struct AttnArgs {
     float scale_log2;          // softmax_scale * log2(e)
 };
 
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
-// contiguous run of (head, query tile) rows so that the workgroups sharing an L2 work on
-// neighbouring query tiles of the same head, whose kept key tiles overlap.
-__device__ inline int64_t xcd_row(int64_t pid, int64_t rows) {
-    constexpr int kXcd = 8;
-    const int64_t xcd = pid % kXcd, local = pid / kXcd;
-    const int64_t base = rows / kXcd, rem = rows % kXcd;
-    return xcd * base + (xcd < rem ? xcd : rem) + local;
-}
+// Workgroups are dealt round-robin to the 8 dies (XCDs), each with its own L2, all sharing
+// the 256 MB memory-side cache.  Die x = blockIdx.x % 8 takes the x-th eighth of every head's
+// query tiles and walks the heads in order: all dies then work on the same head at the same
+// time (its K/V, ~120 MB at 220k tokens, stay in the memory-side cache), and the workgroups
+// sharing an L2 hold neighbouring query tiles, whose kept key tiles overlap.
+// xcd_work() returns false for the padding workgroups of dies with fewer tiles.
 
 __device__ inline int rho(int m) {  // swap bits 2 and 3
     return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
+}
+
+// 16 bytes per lane straight from global memory into LDS: lane i of the wave lands at LDS byte
+// lds_base + 16*i (lds_base wave-uniform), from global address base + voff (base uniform).
+// Written as inline assembly so that the compiler does not serialise later LDS reads of OTHER
+// buffers behind these loads; completion is awaited explicitly (vmcnt) before the barrier that
+// publishes the buffer.  M0 carries the LDS base and is dead outside the statement.
+__device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(base)
+                 : "memory");
+}
+
+__device__ inline bool xcd_work(const int32_t* __restrict__ xcd_cum, const HeadGeom* __restrict__ heads,
+                                int n_heads, int& head, int& qi) {
+    const int x = blockIdx.x % kXcd, local = blockIdx.x / kXcd;
+    const int32_t* cum = xcd_cum + x * (n_heads + 1);
+    if (local >= cum[n_heads]) return false;
+    int h = 0;
+    while (local >= cum[h + 1]) ++h;
+    const int n = heads[h].n_tiles;
+    head = h;
+    qi = x * (n / kXcd) + (x < n % kXcd ? x : n % kXcd) + (local - cum[h]);
+    return true;
 }
 
 template <int D>
@@ -81,19 +103,23 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
     const int r = wave & 1, c = wave >> 1;
     const int lq = lane & 31, hh = lane >> 5;
 
-    const int64_t row = xcd_row(blockIdx.x, a.rows);
-    const int64_t b = row / a.total_tiles;
-    const int64_t g = row - b * a.total_tiles;
-    const int head = a.tile_head[g];
+    int head, qi;
+    if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, head, qi)) return;
     const HeadGeom hg = a.heads[head];
-    const int qi = (int)(g - hg.tile_off);
+    const int64_t b = blockIdx.y;
+    const int64_t row = b * a.total_tiles + hg.tile_off + qi;
     const int beg = a.row_ptr[row];
     const int nsel = a.row_ptr[row + 1] - beg;
-    const int32_t* cols = a.col_idx + beg;
+    // The kept list and the validity masks are read-only for the whole launch and indexed
+    // uniformly: reading them through the constant address space makes them scalar loads, so
+    // no vector-memory counter waits of the compiler's own end up inside the main loop.
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_t;
+    typedef const __attribute__((address_space(4))) uint64_t* const_u64_t;
+    const const_i32_t cols = (const_i32_t)(uintptr_t)(a.col_idx + beg);
     const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
     const char* kt = a.k + head_tile0 * kKBytes;
     const char* vt = a.v + head_tile0 * kVBytes;
-    const uint64_t* vmask = a.valid_mask + hg.tile_off;
+    const const_u64_t vmask = (const_u64_t)(uintptr_t)(a.valid_mask + hg.tile_off);
 
     // Q operand (B matrix of S^T = K Q^T): lane holds query row 32r+lq, channels 16t+8hh..+8.
     bf16x8 qf[D / 16];
@@ -103,46 +129,52 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         for (int t = 0; t < D / 16; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qrow + 32 * t);
     }
 
-    // global -> LDS copy plan: chunk id = tid + 256*j, contiguous in global memory.
-    int k_dst[kLoads], v_dst[kLoads];
+    // global -> LDS copy plan.  Loads go straight from global memory into LDS (no staging
+    // registers): one wave instruction fills 1 KB of LDS, lane i at byte 16*i, so the swizzle
+    // is applied on the global side -- each lane fetches the chunk that belongs at its fixed
+    // LDS position.  Wave w issues instructions w*kLoads .. w*kLoads+kLoads-1 of each tile.
+    int k_src[kLoads], v_src[kLoads];
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-        const int cid = tid + 256 * j;
-        const int krow = cid / kKChunks, kch = cid % kKChunks;
-        k_dst[j] = krow * kRowB + ((kch ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
-        const int vrow = cid >> 3, vch = cid & 7;
-        v_dst[j] = kKBytes + vrow * 128 + ((vch ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
+        const int inst = wave * kLoads + j;
+        const int krow = inst * (1024 / kRowB) + lane / kKChunks, kpos = lane % kKChunks;
+        k_src[j] = krow * kRowB + ((kpos ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
+        const int vrow = inst * 8 + (lane >> 3), vpos = lane & 7;
+        v_src[j] = vrow * 128 + ((vpos ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
     }
-    // Staging registers of the tile in flight (plain unrolled code: the arrays must stay in
-    // VGPRs, so no lambdas or dynamic indexing touch them).
-    u32x4 kreg[kLoads], vreg[kLoads];
-#define VEDA_FETCH(j_tile)                                                            \
-    do {                                                                              \
-        const char* ks_ = kt + (int64_t)(j_tile) * kKBytes + tid * 16;                \
-        const char* vs_ = vt + (int64_t)(j_tile) * kVBytes + tid * 16;                \
-        _Pragma("unroll") for (int j = 0; j < kLoads; ++j) {                          \
-            kreg[j] = *reinterpret_cast<const u32x4*>(ks_ + 4096 * j);                \
-            vreg[j] = *reinterpret_cast<const u32x4*>(vs_ + 4096 * j);                \
-        }                                                                             \
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    const uint32_t wave_lds = smem_base + (uint32_t)__builtin_amdgcn_readfirstlane(wave) * (kLoads * 1024);
+#define VEDA_LOAD_K(j_tile, SLOT)                                                                          \
+    do {                                                                                                   \
+        const char* src_ = kt + (int64_t)(j_tile) * kKBytes;                                               \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
+            dma16_to_lds(wave_lds + (SLOT) * kStage + j * 1024, src_, (uint32_t)k_src[j]);                 \
     } while (0)
-#define VEDA_STASH(stage_)                                                            \
-    do {                                                                              \
-        char* base_ = smem + (stage_) * kStage;                                       \
-        _Pragma("unroll") for (int j = 0; j < kLoads; ++j) {                          \
-            *reinterpret_cast<u32x4*>(base_ + k_dst[j]) = kreg[j];                    \
-            *reinterpret_cast<u32x4*>(base_ + v_dst[j]) = vreg[j];                    \
-        }                                                                             \
+#define VEDA_LOAD_V(j_tile, SLOT)                                                                          \
+    do {                                                                                                   \
+        const char* src_ = vt + (int64_t)(j_tile) * kVBytes;                                               \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
+            dma16_to_lds(wave_lds + (SLOT) * kStage + kKBytes + j * 1024, src_, (uint32_t)v_src[j]);       \
+    } while (0)
+    // All of this wave's LDS-bound loads have landed (vmcnt 0), then meet the other waves.
+#define VEDA_LOADS_DONE_BARRIER()              \
+    do {                                       \
+        __builtin_amdgcn_s_waitcnt(0x0F70);    \
+        __syncthreads();                       \
     } while (0)
 
-    // operand read offsets inside a stage
-    const int k_row_off = (32 * c + rho(lq)) * kRowB;
-    const int k_swz = lq & (kKChunks - 1);
-    int v_row_off[D / 32], v_swz[D / 32];
+    // per-lane operand read offsets inside a slot (swizzle folded in, one register each)
+    const char* k_addr[D / 16];
+    const char* v_addr[D / 32][2];
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t)
+        k_addr[t] = smem + (32 * c + rho(lq)) * kRowB + (((2 * t + hh) ^ (lq & (kKChunks - 1))) << 4);
 #pragma unroll
     for (int nb = 0; nb < D / 32; ++nb) {
         const int vrow = 32 * nb + lq;
-        v_row_off[nb] = kKBytes + vrow * 128;
-        v_swz[nb] = ((vrow >> 1) & 7) ^ ((vrow & 1) << 2);
+        const int swz = ((vrow >> 1) & 7) ^ ((vrow & 1) << 2);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) v_addr[nb][s2] = smem + kKBytes + vrow * 128 + (((4 * c + 2 * s2 + hh) ^ swz) << 4);
     }
 
     f32x16 o[D / 32];
@@ -150,90 +182,118 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
     for (int nb = 0; nb < D / 32; ++nb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[nb][i] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    // Online softmax state of this lane's query over this wave's key subset.  m_ref is the
+    // reference point of the exponentials, not necessarily the running maximum: it is only
+    // moved (and O, l rescaled) when some row's maximum outgrows it by more than 2^kSlack,
+    // which keeps the 64-register rescale off the common path.  Any reference gives the
+    // same O after the final division by l.
+    constexpr float kSlack = 8.0f;
+    float m_ref = -INFINITY, mc = 0.0f, l_run = 0.0f;
 
-    int j_cur = nsel > 0 ? cols[0] : 0;
-    uint64_t vm_cur = nsel > 0 ? vmask[j_cur] : 0ull;
+    // S^T (32 keys x 32 queries) = K_half Q^T from K slot SLOT into DST.
+#define VEDA_QK(DST, SLOT)                                                                             \
+    do {                                                                                               \
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) DST[i] = 0.0f;                                  \
+        _Pragma("unroll") for (int t = 0; t < D / 16; ++t) {                                           \
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_addr[t] + (SLOT) * kStage);           \
+            DST = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], DST, 0, 0, 0);                    \
+        }                                                                                              \
+    } while (0)
+
+    // Step `it` of the kept list, P = it & 1.  On entry LDS holds K(it+1) in K slot P^1 and
+    // V(it) in V slot P, and s_cur = S(it).  The step starts the loads of K(it+2) and V(it+1)
+    // into the slots step it-1 finished with, forms S(it+1) on the matrix cores while the
+    // vector ALUs run the softmax of S(it), then accumulates P V(it).
+    // jA = tile of step it+1, jB = tile of step it+2 (clamped), vmA = mask of jA.
+#define VEDA_STEP(P)                                                                                       \
+    do {                                                                                                   \
+        const bool has1 = it + 1 < nsel, has2 = it + 2 < nsel;                                             \
+        if (has2) VEDA_LOAD_K(jB, (P));                                                                    \
+        if (has1) VEDA_LOAD_V(jA, (P) ^ 1);                                                                \
+        const int jC = cols[it + 3 < nsel ? it + 3 : nsel - 1];                                            \
+        const uint64_t vmB = vmask[jB];                                                                    \
+        f32x16 s_next;                                                                                     \
+        if (has1) VEDA_QK(s_next, (P) ^ 1);                                                                \
+        /* register i of this lane is key slot 32c + 16*(i/8) + 8*hh + (i%8) of the tile */                \
+        if (vm_cur != ~0ull) {                                                                             \
+            const uint32_t half = (uint32_t)(vm_cur >> (32 * c));                                          \
+            _Pragma("unroll") for (int i = 0; i < 16; ++i)                                                 \
+                if (!((half >> (16 * (i >> 3) + 8 * hh + (i & 7))) & 1u)) s_cur[i] = -INFINITY;            \
+        }                                                                                                  \
+        float mloc = s_cur[0];                                                                             \
+        _Pragma("unroll") for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, s_cur[i]);                       \
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));                                                          \
+        if (__any((mloc - m_ref) * a.scale_log2 > kSlack)) {                                               \
+            const float m_new = fmaxf(m_ref, mloc);                                                        \
+            const float m_use = m_new == -INFINITY ? 0.0f : m_new;                                         \
+            const float alpha = __builtin_amdgcn_exp2f((m_ref - m_use) * a.scale_log2);                    \
+            m_ref = m_new;                                                                                 \
+            mc = m_use * a.scale_log2;                                                                     \
+            l_run *= alpha;                                                                                \
+            _Pragma("unroll") for (int nb = 0; nb < D / 32; ++nb)                                          \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) o[nb][i] *= alpha;                          \
+        }                                                                                                  \
+        float psum = 0.0f;                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                   \
+            s_cur[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[i], a.scale_log2, -mc));                \
+            psum += s_cur[i];                                                                              \
+        }                                                                                                  \
+        l_run += psum;                                                                                     \
+        bf16x8 pf[2];                                                                                      \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                                    \
+            pf[0][e] = (__bf16)s_cur[e];                                                                   \
+            pf[1][e] = (__bf16)s_cur[8 + e];                                                               \
+        }                                                                                                  \
+        /* O^T (d x 32 queries) += V^T[:, keys of this half] P^T */                                        \
+        _Pragma("unroll") for (int nb = 0; nb < D / 32; ++nb)                                              \
+            _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                             \
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_addr[nb][s2] + (P) * kStage);  \
+                o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[nb], 0, 0, 0);               \
+            }                                                                                              \
+        if (has1) s_cur = s_next;                                                                          \
+        vm_cur = vmA;                                                                                      \
+        vmA = vmB;                                                                                         \
+        jA = jB;                                                                                           \
+        jB = jC;                                                                                           \
+        VEDA_LOADS_DONE_BARRIER();                                                                         \
+    } while (0)
+
+    f32x16 s_cur;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_cur[i] = 0.0f;
+    uint64_t vm_cur = 0ull, vmA = 0ull;
+    int jA = 0, jB = 0;
     if (nsel > 0) {
-        VEDA_FETCH(j_cur);
-        VEDA_STASH(0);
+        const int j0 = cols[0];
+        jA = cols[nsel > 1 ? 1 : 0];
+        jB = cols[nsel > 2 ? 2 : nsel - 1];
+        vm_cur = vmask[j0];
+        vmA = vmask[jA];
+        VEDA_LOAD_K(j0, 0);
+        VEDA_LOAD_V(j0, 0);
+        if (nsel > 1) VEDA_LOAD_K(jA, 1);
+        VEDA_LOADS_DONE_BARRIER();
+        VEDA_QK(s_cur, 0);
     }
-    __syncthreads();
-
-    for (int it = 0; it < nsel; ++it) {
-        const int stage = it & 1;
-        const bool more = it + 1 < nsel;
-        int j_next = 0;
-        uint64_t vm_next = 0ull;
-        if (more) {
-            j_next = cols[it + 1];
-            vm_next = vmask[j_next];
-            VEDA_FETCH(j_next);
-        }
-        const char* sb = smem + stage * kStage;
-
-        // S^T (32 keys x 32 queries) = K_half Q^T
-        f32x16 s;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.0f;
-#pragma unroll
-        for (int t = 0; t < D / 16; ++t) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sb + k_row_off + (((2 * t + hh) ^ k_swz) << 4));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
-        }
-        // register i of this lane is key slot 32c + 16*(i/8) + 8*hh + (i%8) of the tile
-        if (vm_cur != ~0ull) {
-            const uint32_t half = (uint32_t)(vm_cur >> (32 * c));
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (!((half >> (16 * (i >> 3) + 8 * hh + (i & 7))) & 1u)) s[i] = -INFINITY;
-        }
-        float mloc = s[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, s[i]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_run, mloc);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float mc = m_use * a.scale_log2;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * a.scale_log2);
-        float psum = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -mc));
-            psum += s[i];
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int nb = 0; nb < D / 32; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[nb][i] *= alpha;
-        }
-        bf16x8 pf[2];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            pf[0][e] = (__bf16)s[e];
-            pf[1][e] = (__bf16)s[8 + e];
-        }
-        // O^T (d x 32 queries) += V^T[:, keys of this half] P^T
-#pragma unroll
-        for (int nb = 0; nb < D / 32; ++nb) {
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const int cv = 4 * c + 2 * s2 + hh;
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sb + v_row_off[nb] + ((cv ^ v_swz[nb]) << 4));
-                o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[nb], 0, 0, 0);
-            }
-        }
-        if (more) VEDA_STASH(stage ^ 1);
-        j_cur = j_next;
-        vm_cur = vm_next;
-        __syncthreads();
+    // K slot 0 has been read by every wave before step 0 refills it.  The vmcnt(0) here is on
+    // every path into the loop, so the compiler knows the Q loads are complete and puts no
+    // vector-memory waits of its own between the in-loop prefetches and their consumers.
+    VEDA_LOADS_DONE_BARRIER();
+    int it = 0;
+    for (; it + 1 < nsel; it += 2) {
+        VEDA_STEP(0);
+        ++it;
+        VEDA_STEP(1);
+        --it;
     }
+    if (it < nsel) VEDA_STEP(0);
+    const float m_run = m_ref;
 
-#undef VEDA_FETCH
-#undef VEDA_STASH
+#undef VEDA_LOAD_K
+#undef VEDA_LOAD_V
+#undef VEDA_LOADS_DONE_BARRIER
+#undef VEDA_QK
+#undef VEDA_STEP
     // ---- merge the two key halves, normalise, transpose through LDS, scatter to tokens ----
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     float* xo = reinterpret_cast<float*>(smem) + r * (32 * D + 64);  // [D][32] + m[32] + l[32]
@@ -297,12 +357,11 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a, float 
     __shared__ float ks[kTile * kPitch];
     __shared__ float ps[kTile * (kTile + 1)];
     const int tid = threadIdx.x, q = tid >> 2, part = tid & 3;
-    const int64_t row = xcd_row(blockIdx.x, a.rows);
-    const int64_t b = row / a.total_tiles;
-    const int64_t g = row - b * a.total_tiles;
-    const int head = a.tile_head[g];
+    int head, qi;
+    if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, head, qi)) return;
     const HeadGeom hg = a.heads[head];
-    const int qi = (int)(g - hg.tile_off);
+    const int64_t b = blockIdx.y;
+    const int64_t row = b * a.total_tiles + hg.tile_off + qi;
     const int beg = a.row_ptr[row];
     const int nsel = a.row_ptr[row + 1] - beg;
     const int32_t* cols = a.col_idx + beg;
@@ -414,7 +473,8 @@ extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_t
     a.n_heads = pl->prob.heads; a.T = pl->prob.T; a.H = pl->prob.H; a.W = pl->prob.W;
     a.scale_log2 = softmax_scale * kLog2e;
     hipStream_t s = (hipStream_t)stream;
-    dim3 grid((unsigned)a.rows), block(256);
+    a.xcd_cum = pl->d_xcd_cum;
+    dim3 grid((unsigned)(kXcd * pl->xcd_max_tiles), (unsigned)pl->prob.batch), block(256);
     if (pl->prob.dtype == VEDA_BF16) {
         if (d == 128) {
             constexpr size_t smem = 2 * (64 * 256 + 128 * 128);

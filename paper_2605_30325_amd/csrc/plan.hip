@@ -83,9 +83,24 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
     for (int h = 0; h < p->heads; ++h)
         for (int32_t i = 0; i < pl->heads[h].n_tiles; ++i) tile_head[(size_t)pl->heads[h].tile_off + i] = (uint8_t)h;
 
+    std::vector<int32_t> xcd_cum((size_t)veda::kXcd * (p->heads + 1), 0);
+    for (int x = 0; x < veda::kXcd; ++x) {
+        int32_t acc = 0;
+        for (int h = 0; h < p->heads; ++h) {
+            xcd_cum[(size_t)x * (p->heads + 1) + h] = acc;
+            const int32_t n = pl->heads[h].n_tiles;
+            acc += n / veda::kXcd + (x < n % veda::kXcd ? 1 : 0);
+        }
+        xcd_cum[(size_t)x * (p->heads + 1) + p->heads] = acc;
+        pl->xcd_max_tiles = acc > pl->xcd_max_tiles ? acc : pl->xcd_max_tiles;
+    }
+
     hipError_t e = hipGetDevice(&pl->device);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum, xcd_cum.size() * sizeof(int32_t));
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_xcd_cum, xcd_cum.data(), xcd_cum.size() * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipMemcpy(pl->d_heads, pl->heads.data(), sizeof(HeadGeom) * p->heads, hipMemcpyHostToDevice);
     if (e == hipSuccess)
@@ -103,6 +118,7 @@ void veda_plan_destroy(veda_plan* pl) {
     if (!pl) return;
     if (pl->d_heads) (void)hipFree(pl->d_heads);
     if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
+    if (pl->d_xcd_cum) (void)hipFree(pl->d_xcd_cum);
     delete pl;
 }
 

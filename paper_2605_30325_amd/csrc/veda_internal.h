@@ -14,6 +14,7 @@ namespace veda {
 
 constexpr int kTile = 64;        // B: tokens per tile
 constexpr int kMaxHeads = 128;   // per-call tables passed by value are sized for this
+constexpr int kXcd = 8;          // accelerator dies (each with its own L2); workgroup i runs on die i % 8
 
 // Per-head geometry, one entry per head, in device memory (plan->d_heads).
 struct HeadGeom {
@@ -49,6 +50,11 @@ struct veda_plan {
     int device = -1;
     veda::HeadGeom* d_heads = nullptr;  // device [heads]
     uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
+    // Work split of the attention launch: die x takes the x-th eighth of every head's query
+    // tiles, heads in order, so all dies work on the same head at the same time.
+    // d_xcd_cum[x*(heads+1) + h] = number of query tiles die x owns in heads < h.
+    int32_t* d_xcd_cum = nullptr;       // device [8][heads+1]
+    int32_t xcd_max_tiles = 0;          // max over dies of the die's total
     int elem_size() const { return prob.dtype == VEDA_BF16 ? 2 : 4; }
     int64_t tokens() const { return (int64_t)prob.T * prob.H * prob.W; }
 };
