@@ -200,29 +200,42 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         }                                                                                              \
     } while (0)
 
+    // Value of the lane that holds the other 16 keys of the same query (lane ^ 32).
+    const int swap_addr = (lane ^ 32) << 2;
+#define VEDA_SWAP32(X) __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(swap_addr, __builtin_bit_cast(int, (X))))
+
+    // Row maximum of a raw S^T accumulator: in-register over the lane's 16 keys, then one
+    // exchange with the lane holding the other 16 keys of the same query.
+#define VEDA_ROWMAX(S, M)                                                          \
+    do {                                                                           \
+        M = S[0];                                                                  \
+        _Pragma("unroll") for (int i = 1; i < 16; ++i) M = fmaxf(M, S[i]);         \
+        M = fmaxf(M, VEDA_SWAP32(M));                                              \
+    } while (0)
+
     // Step `it` of the kept list, P = it & 1.  On entry LDS holds K(it+1) in K slot P^1 and
-    // V(it) in V slot P, and s_cur = S(it).  The step starts the loads of K(it+2) and V(it+1)
-    // into the slots step it-1 finished with, forms S(it+1) on the matrix cores while the
-    // vector ALUs run the softmax of S(it), then accumulates P V(it).
+    // V(it) in V slot P; s_cur = S(it) (raw) and mloc = its row maximum.  The step starts the
+    // loads of K(it+2) and V(it+1) into the slots step it-1 finished with.  Two rare branches
+    // come first (edge tiles: mask padded keys; reference moved: rescale).  The rest is one
+    // straight-line block cut into segments by scheduling barriers, one MFMA per segment: an
+    // MFMA holds the matrix pipe for 32 cycles, a plain VALU op issues in 4 and exp2 in 8, so
+    // each S(it+1) MFMA carries the scale-exponentiate-pack work of 2 (d=128) or 4 (d=64)
+    // scores of S(it) in its shadow, and each P V(it) MFMA a share of the row-sum / next
+    // row-maximum bookkeeping.  LDS operand reads are issued kAhead MFMAs early.
     // jA = tile of step it+1, jB = tile of step it+2 (clamped), vmA = mask of jA.
 #define VEDA_STEP(P)                                                                                       \
     do {                                                                                                   \
-        const bool has1 = it + 1 < nsel, has2 = it + 2 < nsel;                                             \
-        if (has2) VEDA_LOAD_K(jB, (P));                                                                    \
-        if (has1) VEDA_LOAD_V(jA, (P) ^ 1);                                                                \
+        if (it + 2 < nsel) VEDA_LOAD_K(jB, (P));                                                           \
+        if (it + 1 < nsel) VEDA_LOAD_V(jA, (P) ^ 1);                                                       \
         const int jC = cols[it + 3 < nsel ? it + 3 : nsel - 1];                                            \
         const uint64_t vmB = vmask[jB];                                                                    \
-        f32x16 s_next;                                                                                     \
-        if (has1) VEDA_QK(s_next, (P) ^ 1);                                                                \
         /* register i of this lane is key slot 32c + 16*(i/8) + 8*hh + (i%8) of the tile */                \
         if (vm_cur != ~0ull) {                                                                             \
             const uint32_t half = (uint32_t)(vm_cur >> (32 * c));                                          \
             _Pragma("unroll") for (int i = 0; i < 16; ++i)                                                 \
                 if (!((half >> (16 * (i >> 3) + 8 * hh + (i & 7))) & 1u)) s_cur[i] = -INFINITY;            \
+            VEDA_ROWMAX(s_cur, mloc);                                                                      \
         }                                                                                                  \
-        float mloc = s_cur[0];                                                                             \
-        _Pragma("unroll") for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, s_cur[i]);                       \
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));                                                          \
         if (__any((mloc - m_ref) * a.scale_log2 > kSlack)) {                                               \
             const float m_new = fmaxf(m_ref, mloc);                                                        \
             const float m_use = m_new == -INFINITY ? 0.0f : m_new;                                         \
@@ -233,24 +246,42 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
             _Pragma("unroll") for (int nb = 0; nb < D / 32; ++nb)                                          \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) o[nb][i] *= alpha;                          \
         }                                                                                                  \
-        float psum = 0.0f;                                                                                 \
-        _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                   \
-            s_cur[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[i], a.scale_log2, -mc));                \
-            psum += s_cur[i];                                                                              \
+        /* ---- straight-line block, issue order pinned segment by segment ---- */                          \
+        /* S(it+1); on the last step this reads a stale slot and the result is dropped */                  \
+        f32x16 s_next;                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) s_next[i] = 0.0f;                                   \
+        bf16x8 fr[2 * G];                                                                                  \
+        bf16x8 pf[2];                                                                                      \
+        float psum = 0.0f, mx0 = -INFINITY;                                                                \
+        _Pragma("unroll") for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f, P);                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                 \
+        _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                    \
+            fr[g + kAhead] = VEDA_FRAG(g + kAhead, P);                                                     \
+            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], qf[g], s_next, 0, 0, 0);               \
+            _Pragma("unroll") for (int e = 0; e < 16 / G; ++e) {                                           \
+                const int i = g * (16 / G) + e;                                                            \
+                s_cur[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[i], a.scale_log2, -mc));            \
+                pf[i >> 3][i & 7] = (__bf16)s_cur[i];                                                      \
+            }                                                                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                             \
+        }                                                                                                  \
+        /* O^T (d x 32 queries) += V^T[:, keys of this half] P^T; bookkeeping rides along */               \
+        _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                    \
+            if (g + kAhead < G) fr[G + g + kAhead] = VEDA_FRAG(G + g + kAhead, P);                         \
+            const int nb = g % (D / 32), s2 = g / (D / 32);                                                \
+            o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[G + g], pf[s2], o[nb], 0, 0, 0);            \
+            _Pragma("unroll") for (int e = 0; e < 16 / G; ++e) psum += s_cur[g * (16 / G) + e];            \
+            if (g >= G / 2) {                                                                              \
+                _Pragma("unroll") for (int e = 0; e < 16 / (G / 2); e += 2) {                              \
+                    const int i = (g - G / 2) * (16 / (G / 2)) + e;                                        \
+                    mx0 = fmaxf(fmaxf(mx0, s_next[i]), s_next[i + 1]);                                     \
+                }                                                                                          \
+            }                                                                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                             \
         }                                                                                                  \
         l_run += psum;                                                                                     \
-        bf16x8 pf[2];                                                                                      \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                                    \
-            pf[0][e] = (__bf16)s_cur[e];                                                                   \
-            pf[1][e] = (__bf16)s_cur[8 + e];                                                               \
-        }                                                                                                  \
-        /* O^T (d x 32 queries) += V^T[:, keys of this half] P^T */                                        \
-        _Pragma("unroll") for (int nb = 0; nb < D / 32; ++nb)                                              \
-            _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                             \
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_addr[nb][s2] + (P) * kStage);  \
-                o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[nb], 0, 0, 0);               \
-            }                                                                                              \
-        if (has1) s_cur = s_next;                                                                          \
+        mloc = fmaxf(mx0, VEDA_SWAP32(mx0));                                                               \
+        s_cur = s_next;                                                                                    \
         vm_cur = vmA;                                                                                      \
         vmA = vmB;                                                                                         \
         jA = jB;                                                                                           \
@@ -258,9 +289,19 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         VEDA_LOADS_DONE_BARRIER();                                                                         \
     } while (0)
 
+    // Operand fragment f of a step: f < G are the K fragments of S(it+1) (K slot P^1), the
+    // rest the V^T fragments of P V(it) (V slot P) in issue order s2-major.
+    constexpr int G = D / 16;
+    constexpr int kAhead = 3;   // LDS reads run this many MFMAs ahead of their consumer
+#define VEDA_FRAG(f, P)                                                                                  \
+    (*reinterpret_cast<const bf16x8*>(                                                                   \
+        (f) < G ? k_addr[(f) < G ? (f) : 0] + ((P) ^ 1) * kStage                                         \
+                : v_addr[((f) < G ? 0 : (f) - G) % (D / 32)][((f) < G ? 0 : (f) - G) / (D / 32)] + (P) * kStage))
+
     f32x16 s_cur;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_cur[i] = 0.0f;
+    float mloc = -INFINITY;
     uint64_t vm_cur = 0ull, vmA = 0ull;
     int jA = 0, jB = 0;
     if (nsel > 0) {
@@ -274,6 +315,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
         if (nsel > 1) VEDA_LOAD_K(jA, 1);
         VEDA_LOADS_DONE_BARRIER();
         VEDA_QK(s_cur, 0);
+        VEDA_ROWMAX(s_cur, mloc);
     }
     // K slot 0 has been read by every wave before step 0 refills it.  The vmcnt(0) here is on
     // every path into the loop, so the compiler knows the Q loads are complete and puts no
@@ -294,6 +336,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a) {
 #undef VEDA_LOADS_DONE_BARRIER
 #undef VEDA_QK
 #undef VEDA_STEP
+#undef VEDA_ROWMAX
+#undef VEDA_FRAG
+#undef VEDA_SWAP32
     // ---- merge the two key halves, normalise, transpose through LDS, scatter to tokens ----
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     float* xo = reinterpret_cast<float*>(smem) + r * (32 * D + 64);  // [D][32] + m[32] + l[32]
