@@ -26,9 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBPS = 8000.0
 
-# HBM bytes per sparse-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/sparse_attn_waver12b_pmc.txt), keyed by workload; None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per sparse-attention launch crossing the L2 -> memory-fabric port, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size
+# (profiles/sparse_attn_waver12b_720p_241f_pmc.txt), keyed by workload; None where not measured.
+MEASURED_TRAFFIC_BYTES = {"waver12b_720p_241f": 2.0 * 136536575 * 1024 + 1317600 * 1024}
 
 
 def parse():
@@ -57,14 +58,14 @@ def cpu_baseline(wl, shapes, kph, dense_flops, q, k, v, eq, ek, score_scale, sof
     *_, idx = vo.estimate_and_select(qf, kf, wl.grid, shape, eq, ek, head, int(kph[head]),
                                      np.float32(score_scale))
     t_prep = time.perf_counter() - t0
-    # attention: sample query tokens until ~10 s of work
+    # attention: sample query tokens for ~15 s of work
     rng = np.random.default_rng(0)
-    n_probe = 64
+    n_probe = min(wl.tokens, 2048)
     queries = np.sort(rng.choice(wl.tokens, size=n_probe, replace=False))
     t0 = time.perf_counter()
     vo.masked_attention(qf, kf, vf, wl.grid, shape, idx, softmax_scale, queries)
     t_probe = time.perf_counter() - t0
-    n_q = int(min(wl.tokens, max(n_probe, 10.0 / max(t_probe / n_probe, 1e-9))))
+    n_q = int(min(wl.tokens, max(n_probe, 15.0 / max(t_probe / n_probe, 1e-9))))
     queries = np.sort(rng.choice(wl.tokens, size=n_q, replace=False))
     t0 = time.perf_counter()
     vo.masked_attention(qf, kf, vf, wl.grid, shape, idx, softmax_scale, queries)
