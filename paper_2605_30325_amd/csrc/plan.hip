@@ -65,7 +65,7 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
         g.n_tiles = (int32_t)n;
         g.tile_off = (int32_t)toff;
         g.score_off = soff;
-        g.score_blk_dim = (int32_t)((n + 63) / 64);
+        g.score_blk_dim = (int32_t)((n + 127) / 128);
         g.score_blk_off = (int32_t)boff;
         toff += n;
         soff += n * n;
@@ -83,6 +83,11 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
     for (int h = 0; h < p->heads; ++h)
         for (int32_t i = 0; i < pl->heads[h].n_tiles; ++i) tile_head[(size_t)pl->heads[h].tile_off + i] = (uint8_t)h;
 
+    std::vector<int32_t> row_blk;
+    for (int h = 0; h < p->heads; ++h)
+        for (int32_t i = 0; i < (pl->heads[h].n_tiles + 63) / 64; ++i) row_blk.push_back((int32_t)((uint32_t)h << 24 | (uint32_t)i));
+    pl->row_blocks = (int64_t)row_blk.size();
+
     std::vector<int32_t> xcd_cum((size_t)veda::kXcd * (p->heads + 1), 0);
     for (int x = 0; x < veda::kXcd; ++x) {
         int32_t acc = 0;
@@ -99,6 +104,9 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum, xcd_cum.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_row_blk, row_blk.size() * sizeof(int32_t));
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_row_blk, row_blk.data(), row_blk.size() * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipMemcpy(pl->d_xcd_cum, xcd_cum.data(), xcd_cum.size() * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess)
@@ -119,6 +127,7 @@ void veda_plan_destroy(veda_plan* pl) {
     if (pl->d_heads) (void)hipFree(pl->d_heads);
     if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
     if (pl->d_xcd_cum) (void)hipFree(pl->d_xcd_cum);
+    if (pl->d_row_blk) (void)hipFree(pl->d_row_blk);
     delete pl;
 }
 

@@ -95,106 +95,159 @@ struct MlpDev {
     const float *w1, *b1, *w2, *b2;
 };
 
-constexpr int kMlpRows = 16;
-constexpr int kMlpThreads = 128;
+constexpr int kMlpRows = 64;       // tiles per workgroup
+constexpr int kMlpCols = 128;      // output units per pass
+constexpr int kMlpK = 32;          // reduction indices staged per step
+constexpr int kMlpThreads = 256;
+constexpr int kMlpXPitch = kMlpK + 4;   // floats; keeps every staged row 16-byte aligned
 
-// One workgroup projects up to 16 consecutive tiles of one head.  Descriptors sit in LDS and
-// are read as broadcasts; each thread owns output units and keeps 16 running chains.
-// grid = (ceil(total_tiles/16) [blocks never mix heads' weights: see the while loop], 2, batch)
-__global__ __launch_bounds__(kMlpThreads) void mlp_kernel(const HeadGeom* __restrict__ heads,
-                                                         const uint8_t* __restrict__ tile_head,
-                                                         const float* __restrict__ zq, const float* __restrict__ zk,
-                                                         float* __restrict__ yq, float* __restrict__ yk,
-                                                         MlpDev pq, MlpDev pk, int64_t total_tiles) {
-    extern __shared__ float smem[];
-    const MlpDev p = blockIdx.y == 0 ? pq : pk;
-    const float* z = blockIdx.y == 0 ? zq : zk;
-    float* y = blockIdx.y == 0 ? yq : yk;
-    const int64_t b = blockIdx.z;
-    float* zs = smem;                          // [16][in_dim]
-    float* hs = smem + kMlpRows * p.in_dim;    // [16][hidden]
-    const int64_t g_begin = (int64_t)blockIdx.x * kMlpRows;
-    const int64_t g_end = g_begin + kMlpRows < total_tiles ? g_begin + kMlpRows : total_tiles;
-    int64_t g = g_begin;
-    while (g < g_end) {
-        const int head = tile_head[g];
-        const int64_t head_end = (int64_t)heads[head].tile_off + heads[head].n_tiles;
-        const int64_t stop = head_end < g_end ? head_end : g_end;
-        const int rows = (int)(stop - g);
-        const float* zsrc = z + (b * total_tiles + g) * p.in_dim;
-        __syncthreads();
-        for (int t = threadIdx.x; t < kMlpRows * p.in_dim; t += kMlpThreads)
-            zs[t] = t < rows * p.in_dim ? zsrc[t] : 0.0f;
-        __syncthreads();
-        const int first_out = p.hidden ? p.hidden : p.out_dim;
-        const float* w1 = p.w1 + (int64_t)head * p.in_dim * first_out;
-        const float* b1 = p.b1 + (int64_t)head * first_out;
-        for (int j = threadIdx.x; j < first_out; j += kMlpThreads) {
-            float acc[kMlpRows];
-            const float bias = b1[j];
+// One affine layer for the 64 rows of a workgroup:
+//   out[r][n] = act(bias[n] + sum_k x[r][k] * w[k][n]),  one fmaf chain per (r,n), k ascending.
+// Thread (rg = tid/32, jg = tid%32) keeps rows 8*rg..+7 x outputs c0+4*jg..+3 in registers.  The
+// weights of 32 reduction indices x 128 outputs are staged in LDS per step (ws); the inputs come
+// either from global memory, staged alongside (xs), or from a resident LDS array (x_lds).
+// Results go to an LDS array (y_lds, pitch ldy) or to global rows (y_glb, pitch N).
+template <bool kXGlobal, bool kYLds>
+__device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const float* x_lds, int ldx, int rows,
+                                          int K, const float* __restrict__ w, const float* __restrict__ bias,
+                                          int N, bool relu, float* y_lds, int ldy, float* __restrict__ y_glb,
+                                          float* xs, float* ws) {
+    const int jg = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    for (int c0 = 0; c0 < N; c0 += kMlpCols) {
+        float acc[8][4];
 #pragma unroll
-            for (int r = 0; r < kMlpRows; ++r) acc[r] = bias;
-            for (int i = 0; i < p.in_dim; i += 4) {   // in_dim = 3*head_dim is a multiple of 4
-                float w[4];
+        for (int e = 0; e < 4; ++e) {
+            const int n = c0 + 4 * jg + e;
+            const float bv = n < N ? bias[n] : 0.0f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = w1[(int64_t)(i + e) * first_out + j];
-#pragma unroll
-                for (int r = 0; r < kMlpRows; ++r) {
-                    const float4 zv = *reinterpret_cast<const float4*>(zs + r * p.in_dim + i);
-                    acc[r] = __builtin_fmaf(zv.x, w[0], acc[r]);
-                    acc[r] = __builtin_fmaf(zv.y, w[1], acc[r]);
-                    acc[r] = __builtin_fmaf(zv.z, w[2], acc[r]);
-                    acc[r] = __builtin_fmaf(zv.w, w[3], acc[r]);
-                }
-            }
-            if (p.hidden) {
-#pragma unroll
-                for (int r = 0; r < kMlpRows; ++r)
-                    hs[r * p.hidden + j] = (p.relu && !(acc[r] > 0.0f)) ? 0.0f : acc[r];
-            } else {
-#pragma unroll
-                for (int r = 0; r < kMlpRows; ++r)
-                    if (r < rows) y[(b * total_tiles + g + r) * p.out_dim + j] = acc[r];
-            }
+            for (int r = 0; r < 8; ++r) acc[r][e] = bv;
         }
-        if (p.hidden) {
+        for (int k0 = 0; k0 < K; k0 += kMlpK) {
+            const int kc = K - k0 < kMlpK ? K - k0 : kMlpK;
             __syncthreads();
-            const float* w2 = p.w2 + (int64_t)head * p.hidden * p.out_dim;
-            const float* b2 = p.b2 + (int64_t)head * p.out_dim;
-            for (int o = threadIdx.x; o < p.out_dim; o += kMlpThreads) {
-                float acc[kMlpRows];
-                const float bias = b2[o];
-#pragma unroll
-                for (int r = 0; r < kMlpRows; ++r) acc[r] = bias;
-                for (int j = 0; j < p.hidden; ++j) {
-                    const float w = w2[(int64_t)j * p.out_dim + o];
-#pragma unroll
-                    for (int r = 0; r < kMlpRows; ++r) acc[r] = __builtin_fmaf(hs[r * p.hidden + j], w, acc[r]);
+            for (int t = threadIdx.x; t < kMlpK * kMlpCols; t += kMlpThreads) {
+                const int i = t / kMlpCols, c = t % kMlpCols;
+                ws[t] = (i < kc && c0 + c < N) ? w[(int64_t)(k0 + i) * N + c0 + c] : 0.0f;
+            }
+            if (kXGlobal) {
+                for (int t = threadIdx.x; t < kMlpRows * (kMlpK / 4); t += kMlpThreads) {
+                    const int r = t / (kMlpK / 4), i4 = (t % (kMlpK / 4)) * 4;   // K is a multiple of 4 here
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (r < rows && i4 < kc) v = *reinterpret_cast<const float4*>(x_glb + (int64_t)r * K + k0 + i4);
+                    *reinterpret_cast<float4*>(xs + r * kMlpXPitch + i4) = v;
                 }
+            }
+            __syncthreads();
+            const float* xb = kXGlobal ? xs + (8 * rg) * kMlpXPitch : x_lds + (8 * rg) * ldx + k0;
+            const int xp = kXGlobal ? kMlpXPitch : ldx;
+            int kk = 0;
+            for (; kk + 4 <= kc; kk += 4) {
+                float4 wv[4];
 #pragma unroll
-                for (int r = 0; r < kMlpRows; ++r)
-                    if (r < rows) y[(b * total_tiles + g + r) * p.out_dim + o] = acc[r];
+                for (int e = 0; e < 4; ++e) wv[e] = *reinterpret_cast<const float4*>(ws + (kk + e) * kMlpCols + 4 * jg);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float4 xv = *reinterpret_cast<const float4*>(xb + r * xp + kk);
+                    acc[r][0] = __builtin_fmaf(xv.x, wv[0].x, acc[r][0]);
+                    acc[r][1] = __builtin_fmaf(xv.x, wv[0].y, acc[r][1]);
+                    acc[r][2] = __builtin_fmaf(xv.x, wv[0].z, acc[r][2]);
+                    acc[r][3] = __builtin_fmaf(xv.x, wv[0].w, acc[r][3]);
+                    acc[r][0] = __builtin_fmaf(xv.y, wv[1].x, acc[r][0]);
+                    acc[r][1] = __builtin_fmaf(xv.y, wv[1].y, acc[r][1]);
+                    acc[r][2] = __builtin_fmaf(xv.y, wv[1].z, acc[r][2]);
+                    acc[r][3] = __builtin_fmaf(xv.y, wv[1].w, acc[r][3]);
+                    acc[r][0] = __builtin_fmaf(xv.z, wv[2].x, acc[r][0]);
+                    acc[r][1] = __builtin_fmaf(xv.z, wv[2].y, acc[r][1]);
+                    acc[r][2] = __builtin_fmaf(xv.z, wv[2].z, acc[r][2]);
+                    acc[r][3] = __builtin_fmaf(xv.z, wv[2].w, acc[r][3]);
+                    acc[r][0] = __builtin_fmaf(xv.w, wv[3].x, acc[r][0]);
+                    acc[r][1] = __builtin_fmaf(xv.w, wv[3].y, acc[r][1]);
+                    acc[r][2] = __builtin_fmaf(xv.w, wv[3].z, acc[r][2]);
+                    acc[r][3] = __builtin_fmaf(xv.w, wv[3].w, acc[r][3]);
+                }
+            }
+            for (; kk < kc; ++kk) {   // tail of a reduction length that is not a multiple of 4
+                const float4 wv = *reinterpret_cast<const float4*>(ws + kk * kMlpCols + 4 * jg);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float xv = xb[r * xp + kk];
+                    acc[r][0] = __builtin_fmaf(xv, wv.x, acc[r][0]);
+                    acc[r][1] = __builtin_fmaf(xv, wv.y, acc[r][1]);
+                    acc[r][2] = __builtin_fmaf(xv, wv.z, acc[r][2]);
+                    acc[r][3] = __builtin_fmaf(xv, wv.w, acc[r][3]);
+                }
             }
         }
-        g = stop;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int row = 8 * rg + r;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = c0 + 4 * jg + e;
+                const float v = (relu && !(acc[r][e] > 0.0f)) ? 0.0f : acc[r][e];
+                if (n < N) {
+                    if (kYLds) y_lds[row * ldy + n] = v;
+                    else if (row < rows) y_glb[(int64_t)row * N + n] = v;
+                }
+            }
+        }
     }
 }
 
-constexpr int kSB = 64;       // score block edge
-constexpr int kSPitch = 68;   // LDS pitch of one latent row (floats)
+// One workgroup projects up to 64 consecutive tiles of one head (Eq. 5, phi_q or phi_k).
+// row_blk[x] = head << 24 | index of the 64-tile block inside that head.
+// grid = (row blocks of all heads, 2 estimators, batch); dynamic LDS = staging + hidden layer.
+__global__ __launch_bounds__(kMlpThreads) void mlp_kernel(const HeadGeom* __restrict__ heads,
+                                                         const int32_t* __restrict__ row_blk,
+                                                         const float* __restrict__ zq, const float* __restrict__ zk,
+                                                         float* __restrict__ yq, float* __restrict__ yk,
+                                                         MlpDev pq, MlpDev pk, int64_t total_tiles) {
+    extern __shared__ __align__(16) float smem[];
+    const MlpDev p = blockIdx.y == 0 ? pq : pk;
+    const float* z = blockIdx.y == 0 ? zq : zk;
+    float* y = blockIdx.y == 0 ? yq : yk;
+    float* ws = smem;                                   // [32][128]
+    float* xs = ws + kMlpK * kMlpCols;                  // [64][36]
+    float* hs = xs + kMlpRows * kMlpXPitch;             // [64][ldh]
+    const int32_t code = row_blk[blockIdx.x];
+    const int head = code >> 24, blk = code & 0xffffff;
+    const HeadGeom hg = heads[head];
+    const int rows = hg.n_tiles - blk * kMlpRows < kMlpRows ? hg.n_tiles - blk * kMlpRows : kMlpRows;
+    const int64_t row0 = (int64_t)blockIdx.z * total_tiles + hg.tile_off + (int64_t)blk * kMlpRows;
+    const float* x = z + row0 * p.in_dim;
+    float* out = y + row0 * p.out_dim;
+    if (p.hidden) {
+        const int ldh = (p.hidden + 3) & ~3;
+        mlp_layer<true, true>(x, nullptr, 0, rows, p.in_dim, p.w1 + (int64_t)head * p.in_dim * p.hidden,
+                  p.b1 + (int64_t)head * p.hidden, p.hidden, p.relu != 0, hs, ldh, nullptr, xs, ws);
+        mlp_layer<false, false>(nullptr, hs, ldh, rows, p.hidden, p.w2 + (int64_t)head * p.hidden * p.out_dim,
+                  p.b2 + (int64_t)head * p.out_dim, p.out_dim, false, nullptr, 0, out, xs, ws);
+    } else {
+        mlp_layer<true, false>(x, nullptr, 0, rows, p.in_dim, p.w1 + (int64_t)head * p.in_dim * p.out_dim,
+                  p.b1 + (int64_t)head * p.out_dim, p.out_dim, false, nullptr, 0, out, xs, ws);
+    }
+}
 
-// One workgroup computes a 64x64 block of one head's score matrix; each thread a 4x4 patch
-// (rows 4*ti..+3, columns tj+16*e).  Latent vectors are staged transposed in LDS, 64 latent
-// coordinates at a time, and consumed in ascending order.
+constexpr int kSB = 128;      // score block edge
+constexpr int kSC = 32;       // latent coordinates staged per step
+constexpr int kSPitch = 36;   // LDS pitch of one staged latent row (floats): rows stay 16-byte
+                              // aligned and 8 consecutive rows start in 8 different bank groups
+
+// One workgroup computes a 128x128 block of one head's score matrix (Eq. 5); thread (ti,tj)
+// keeps the 8x8 patch rows ti+16a, columns tj+16e.  Latent rows are staged row-major in LDS,
+// 64 coordinates at a time; every score is one fmaf chain over ascending coordinate from +0.
 __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
                                                     const float* __restrict__ yq, const float* __restrict__ yk,
                                                     float* __restrict__ scores, int dp, float scale,
                                                     int64_t total_tiles, int64_t score_elems) {
-    __shared__ float qs[kSB * kSPitch];
-    __shared__ float ks[kSB * kSPitch];
-    int head = 0;
-    while (head + 1 < n_heads && (int)blockIdx.x >= heads[head + 1].score_blk_off) ++head;
-    const HeadGeom hg = heads[head];
+    __shared__ __align__(16) float qs[kSB * kSPitch];
+    __shared__ __align__(16) float ks[kSB * kSPitch];
+    int lo = 0, hi = n_heads - 1;   // last head whose first block is <= blockIdx.x
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int)blockIdx.x >= heads[mid].score_blk_off) lo = mid; else hi = mid - 1;
+    }
+    const HeadGeom hg = heads[lo];
     const int blk = blockIdx.x - hg.score_blk_off;
     const int bi = blk / hg.score_blk_dim, bj = blk - bi * hg.score_blk_dim;
     const int64_t b = blockIdx.y;
@@ -202,46 +255,51 @@ __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__
     const float* qbase = yq + (b * total_tiles + hg.tile_off) * dp;
     const float* kbase = yk + (b * total_tiles + hg.tile_off) * dp;
     const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
-    float acc[4][4];
+    float acc[8][8];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 8; ++a)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[a][e] = 0.0f;
-    for (int c0 = 0; c0 < dp; c0 += kSB) {
-        const int cn = dp - c0 < kSB ? dp - c0 : kSB;   // multiple of 4
+        for (int e = 0; e < 8; ++e) acc[a][e] = 0.0f;
+    for (int c0 = 0; c0 < dp; c0 += kSC) {
+        const int cn = dp - c0 < kSC ? dp - c0 : kSC;   // multiple of 4
         __syncthreads();
-        for (int t = threadIdx.x; t < kSB * (kSB / 4); t += 256) {
-            const int r = t / (kSB / 4), c4 = (t % (kSB / 4)) * 4;
+        for (int t = threadIdx.x; t < kSB * (kSC / 4); t += 256) {
+            const int r = t / (kSC / 4), c4 = (t % (kSC / 4)) * 4;
             float4 qv = make_float4(0.f, 0.f, 0.f, 0.f), kv = qv;
             if (c4 < cn) {
                 if (bi * kSB + r < nT) qv = *reinterpret_cast<const float4*>(qbase + (int64_t)(bi * kSB + r) * dp + c0 + c4);
                 if (bj * kSB + r < nT) kv = *reinterpret_cast<const float4*>(kbase + (int64_t)(bj * kSB + r) * dp + c0 + c4);
             }
-            qs[(c4 + 0) * kSPitch + r] = qv.x; qs[(c4 + 1) * kSPitch + r] = qv.y;
-            qs[(c4 + 2) * kSPitch + r] = qv.z; qs[(c4 + 3) * kSPitch + r] = qv.w;
-            ks[(c4 + 0) * kSPitch + r] = kv.x; ks[(c4 + 1) * kSPitch + r] = kv.y;
-            ks[(c4 + 2) * kSPitch + r] = kv.z; ks[(c4 + 3) * kSPitch + r] = kv.w;
+            *reinterpret_cast<float4*>(qs + r * kSPitch + c4) = qv;
+            *reinterpret_cast<float4*>(ks + r * kSPitch + c4) = kv;
         }
         __syncthreads();
-        for (int c = 0; c < cn; ++c) {
-            const float4 qv = *reinterpret_cast<const float4*>(qs + c * kSPitch + 4 * ti);
-            const float qa[4] = {qv.x, qv.y, qv.z, qv.w};
-            float kb[4];
+        for (int c = 0; c < cn; c += 4) {
+            float4 kb[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) kb[e] = ks[c * kSPitch + tj + 16 * e];
+            for (int e = 0; e < 8; ++e) kb[e] = *reinterpret_cast<const float4*>(ks + (tj + 16 * e) * kSPitch + c);
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
+            for (int a = 0; a < 8; ++a) {
+                const float4 qa = *reinterpret_cast<const float4*>(qs + (ti + 16 * a) * kSPitch + c);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[a][e] = __builtin_fmaf(qa[a], kb[e], acc[a][e]);
+                for (int e = 0; e < 8; ++e) {
+                    float v = acc[a][e];
+                    v = __builtin_fmaf(qa.x, kb[e].x, v);
+                    v = __builtin_fmaf(qa.y, kb[e].y, v);
+                    v = __builtin_fmaf(qa.z, kb[e].z, v);
+                    v = __builtin_fmaf(qa.w, kb[e].w, v);
+                    acc[a][e] = v;
+                }
+            }
         }
     }
     float* sbase = scores + b * score_elems + hg.score_off;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const int i = bi * kSB + 4 * ti + a;
+    for (int a = 0; a < 8; ++a) {
+        const int i = bi * kSB + ti + 16 * a;
         if (i >= nT) continue;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < 8; ++e) {
             const int j = bj * kSB + tj + 16 * e;
             if (j < nT) sbase[(int64_t)i * nT + j] = acc[a][e] * scale;
         }
@@ -304,9 +362,12 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
     MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
     const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
-    const size_t smem = sizeof(float) * (size_t)kMlpRows * (size_t)(3 * d + max_hidden);
-    dim3 mgrid((unsigned)((total + kMlpRows - 1) / kMlpRows), 2, (unsigned)pl->prob.batch);
-    hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_tile_head, zq, zk, yq,
+    const size_t smem = sizeof(float) * ((size_t)kMlpK * kMlpCols + (size_t)kMlpRows * kMlpXPitch +
+                                         (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3));
+    if (smem > 64 * 1024)
+        VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    dim3 mgrid((unsigned)pl->row_blocks, 2, (unsigned)pl->prob.batch);
+    hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_row_blk, zq, zk, yq,
                        yk, pq, pk, total);
     st = launch_status("mlp_kernel");
     if (st != VEDA_OK) return st;

@@ -23,8 +23,8 @@ struct HeadGeom {
     int32_t n_tiles;         // nt*nh*nw
     int32_t tile_off;        // first global tile index of this head
     int64_t score_off;       // first score element of this head (per batch)
-    int32_t score_blk_off;   // first 64x64 score block of this head
-    int32_t score_blk_dim;   // ceil(n_tiles / 64)
+    int32_t score_blk_off;   // first 128x128 score block of this head
+    int32_t score_blk_dim;   // ceil(n_tiles / 128)
 };
 
 #if defined(__HIPCC__)
@@ -50,6 +50,10 @@ struct veda_plan {
     int device = -1;
     veda::HeadGeom* d_heads = nullptr;  // device [heads]
     uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
+    // Blocks of 64 consecutive tiles that never straddle two heads (the projection kernel's work
+    // items): d_row_blk[x] = head << 24 | block index inside the head.
+    int32_t* d_row_blk = nullptr;       // device [row_blocks]
+    int64_t row_blocks = 0;
     // Work split of the attention launch: die x takes the x-th eighth of every head's query
     // tiles, heads in order, so all dies work on the same head at the same time.
     // d_xcd_cum[x*(heads+1) + h] = number of query tiles die x owns in heads < h.

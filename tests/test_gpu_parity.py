@@ -60,6 +60,47 @@ def test_batch_two_and_strided_input():
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.mark.parametrize("hidden,dp,relu", [(0, 12, True), (20, 12, True), (131, 8, False), (260, 200, True)])
+def test_estimator_shapes_bit_exact(hidden, dp, relu):
+    # widths that are not multiples of the kernel's blocking, a single affine layer, no ReLU;
+    # 135..180 tiles per head: several 64-row blocks and 128x128 score blocks, all with ragged tails
+    wl = wlm.custom_workload(f"mlp_{hidden}_{dp}", 2, 64, "f32", (10, 20, 36), True, (50, 100), seed=21,
+                             latent_dim=dp)
+    _say(f"[parity] {wl.name}: estimator 192 -> {hidden} -> {dp} relu={relu}")
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    rng = np.random.default_rng(77 + hidden)
+    first = hidden if hidden else dp
+
+    def weights():
+        w1 = rng.uniform(-0.1, 0.1, (wl.heads, 3 * wl.head_dim, first)).astype(np.float32)
+        b1 = rng.uniform(-0.05, 0.05, (wl.heads, first)).astype(np.float32)
+        if not hidden:
+            return w1, b1, None, None
+        return (w1, b1, rng.uniform(-0.2, 0.2, (wl.heads, hidden, dp)).astype(np.float32),
+                rng.uniform(-0.05, 0.05, (wl.heads, dp)).astype(np.float32))
+
+    wq, wk = weights(), weights()
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    scale = hz.score_scale_of(wl)
+    s, _ = veda.veda_tile_score(plan, qt, kt, vm, veda.Mlp(*wq, relu, dev), veda.Mlp(*wk, relu, dev), scale)
+    torch.cuda.synchronize()
+    for h in range(wl.heads):
+        shape = tuple(int(x) for x in shapes[h])
+        lat = []
+        for x, w in ((q, wq), (k, wk)):
+            z = vo.trippool(hz.to_f32_numpy(x[0, h]), wl.grid, shape)
+            lat.append(vo.mlp(z, w[0][h], w[1][h], None if w[2] is None else w[2][h],
+                              None if w[3] is None else w[3][h], relu))
+        ref = vo.score(lat[0], lat[1], np.float32(scale))
+        nt, soff = plan.tiles[h], plan.score_offset[h]
+        got = s[0, soff:soff + nt * nt].view(nt, nt).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"{wl.name} head {h}: scores not bit-exact"
+
+
 def test_zero_sparsity_equals_dense_attention_on_gpu():
     wl = wlm.custom_workload("dense_identity", 3, 128, "bf16", (6, 9, 11), True, (1, 1), seed=13)
     run = hz.run_gpu_path(wl)
@@ -110,12 +151,49 @@ def test_select_long_rows_use_every_instantiation():
         rows = min(nt, 48)
         s = np.random.default_rng(nt).standard_normal((nt, nt)).astype(np.float32)
         s[rows:] = 0.0
-        k = max(1, nt // 20)
+        # 5 % kept: rows of 1024 tiles and more take the sampled-pivot kernel; 50 % kept: the
+        # register-resident (or memory-resident) full search
+        for k in (max(1, nt // 20), nt // 2):
+            _say(f"[parity] select grid {grid}: {nt} tiles, k {k}")
+            rp, ci = veda.veda_tile_select(plan, torch.as_tensor(s).reshape(1, -1).cuda(), [k])
+            torch.cuda.synchronize()
+            got = ci.cpu().numpy().reshape(nt, k)
+            assert np.array_equal(got[:rows], vo.select(s[:rows], k)), (grid, k)
+            assert np.array_equal(got[rows:], np.tile(np.arange(k), (nt - rows, 1))), (grid, k)
+
+
+def test_select_sampled_pivot_paths():
+    # 2048-tile rows at 5 % kept go through the sampled-pivot kernel.  Rows are built so that the
+    # candidate list comes out well sized, too short (large values only where the sample looks),
+    # too long (mass ties at the threshold), and with NaN / infinities / signed zeros in it.
+    shapes = np.asarray([[1, 8, 8]], np.int32)
+    plan = veda.Plan(1, 1, 64, (64, 32, 64), shapes, torch.float32)
+    nt = plan.tiles[0]
+    assert nt == 2048
+    rng = np.random.default_rng(5)
+    s = np.zeros((nt, nt), np.float32)
+    rows = 40
+    s[:8] = rng.standard_normal((8, nt))
+    s[8:12] = rng.integers(-3, 4, size=(4, nt))                       # 7 levels: long tie runs
+    s[12:16] = rng.standard_normal((4, nt))
+    s[12:16, ::8] += 10.0                                             # the 256 sampled columns are the large ones
+    s[16:20] = rng.standard_normal((4, nt))
+    s[16:20, rng.integers(0, nt, 300)] = np.inf
+    s[20:24] = rng.standard_normal((4, nt))
+    s[20:24, rng.integers(0, nt, 1900)] = np.nan
+    s[24:28] = np.where(rng.random((4, nt)) < 0.5, -0.0, 0.0)
+    s[28:32] = -np.inf
+    s[28:32, rng.integers(0, nt, 50)] = 1.0
+    s[32:36] = rng.standard_normal((4, nt)).astype(np.float32) * 1e-30   # tiny values near the zero keys
+    s[36:40] = -np.abs(rng.standard_normal((4, nt)))                  # all negative
+    for k in (1, 64, 102, 180):
+        _say(f"[parity] sampled select: k {k}")
         rp, ci = veda.veda_tile_select(plan, torch.as_tensor(s).reshape(1, -1).cuda(), [k])
         torch.cuda.synchronize()
         got = ci.cpu().numpy().reshape(nt, k)
-        assert np.array_equal(got[:rows], vo.select(s[:rows], k)), grid
-        assert np.array_equal(got[rows:], np.tile(np.arange(k), (nt - rows, 1))), grid
+        ref = vo.select(s[:rows], k)
+        for r in range(rows):
+            assert np.array_equal(got[r], ref[r]), (k, r)
 
 
 def test_gpu_argument_errors_launch_nothing():
