@@ -1,0 +1,74 @@
+// Declarations shared by the attention kernels: launch arguments, vector types, the direct
+// global->LDS load and the die-aware work split.  Not part of the public ABI.
+#pragma once
+
+#include "veda_internal.h"
+
+namespace veda {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnArgs {
+    const HeadGeom* heads;
+    const uint8_t* tile_head;
+    const int32_t* xcd_cum;
+    const char* q;
+    const char* k;
+    const char* v;
+    const uint64_t* valid_mask;
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    char* out;
+    float* lse;
+    int64_t total_tiles, rows;
+    int64_t so_b, so_h, so_n;  // output strides in bytes
+    int64_t tokens;
+    int n_heads, T, H, W;
+    float scale_log2;          // softmax_scale * log2(e)
+};
+
+// Workgroups are dealt round-robin to the 8 dies (XCDs), each with its own L2, all sharing
+// the 256 MB memory-side cache.  Die x = blockIdx.x % 8 takes the x-th eighth of every head's
+// query tiles and walks the heads in order: all dies then work on the same head at the same
+// time (its K/V, ~120 MB at 220k tokens, stay in the memory-side cache), and the workgroups
+// sharing an L2 hold neighbouring query tiles, whose kept key tiles overlap.
+// The work item is a query tile (unit = 1) or a pair of adjacent query tiles (unit = 2);
+// xcd_cum is the matching table of the plan.  Returns false for the padding workgroups of dies
+// with fewer items.
+__device__ inline bool xcd_work(const int32_t* __restrict__ xcd_cum, const HeadGeom* __restrict__ heads,
+                                int n_heads, int unit, int& head, int& item) {
+    const int x = blockIdx.x % kXcd, local = blockIdx.x / kXcd;
+    const int32_t* cum = xcd_cum + x * (n_heads + 1);
+    if (local >= cum[n_heads]) return false;
+    int h = 0;
+    while (local >= cum[h + 1]) ++h;
+    const int n = (heads[h].n_tiles + unit - 1) / unit;
+    head = h;
+    item = x * (n / kXcd) + (x < n % kXcd ? x : n % kXcd) + (local - cum[h]);
+    return true;
+}
+
+__device__ inline int rho(int m) {  // swap bits 2 and 3
+    return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
+}
+
+// 16 bytes per lane straight from global memory into LDS: lane i of the wave lands at LDS byte
+// lds_base + 16*i (lds_base wave-uniform), from global address base + voff (base uniform).
+// Written as inline assembly so that the compiler does not serialise later LDS reads of OTHER
+// buffers behind these loads; completion is awaited explicitly (vmcnt) before the barrier that
+// publishes the buffer.  M0 carries the LDS base and is dead outside the statement.
+__device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(base)
+                 : "memory");
+}
+
+// Launches the query-tile-pair bf16 kernel (attn_pair.hip); a.xcd_cum must be the pair table.
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, hipStream_t s);
+
+}  // namespace veda

@@ -1,0 +1,403 @@
+// Stage 4, bf16, query-tile-pair kernel (Eq. 2; Sec. 4.3 tile skipping; Alg. 1 "UnTile").
+//
+// A compute unit can pull K/V tiles from L2 into LDS at 64 bytes per clock at most, and a kept
+// tile pair needs 32 KB of them for 512 matrix-pipe cycles of work: with one query tile per
+// workgroup the loads, not the matrix cores, set the pace.  Neighbouring query tiles keep
+// largely the same key tiles, so here one workgroup owns TWO adjacent query tiles and walks
+// the union of their two kept lists: a key tile kept by both is loaded once and used twice.
+//
+// Four wavefronts: waves 0,1 hold rows 0-31 / 32-63 of query tile A = 2p, waves 2,3 those of
+// tile B = 2p+1.  Every wave attends to all 64 slots of a key tile, so it needs no merge with
+// another wave at the end.  A wave whose query tile does not keep the current key tile skips
+// the step and only meets the others at the barrier; the matrix cores it leaves idle go to the
+// second workgroup resident on the compute unit.
+//
+// The products are formed transposed (S^T = K Q^T, O^T = V^T P^T): a lane owns one query, its
+// accumulator registers run over keys, P^T in registers already is the B operand of the second
+// product.  K rows are loaded permuted by rho (bits 2,3 swapped) so that the eight keys a
+// lane-half owns are contiguous in the channel-major V tile.  One step of one wave:
+//     S^T block 0 (8 MFMA) | S^T block 1 (8 MFMA; the row maximum of block 0 in its shadow)
+//     row maximum, reference check, first 8 exponentials          (matrix pipe idle: other wave)
+//     4 x [ 4 MFMA of O^T += V^T P^T ; the next 8 exponentials in their shadow ]
+// K/V tiles are double buffered (2 x 32 KB at d = 128) and filled by direct global->LDS loads
+// issued one step ahead.
+#include "attn_common.h"
+
+namespace veda {
+
+typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
+__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) { return *(lds_bf16x8_ptr)(uintptr_t)addr; }
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+constexpr float kPairSlack = 8.0f;   // log2 units a row maximum may outgrow the softmax reference
+
+// Online-softmax state of one wave: 32 queries of one query tile (one per lane, duplicated in
+// the two lane halves).  qf holds Q scaled by softmax_scale*log2(e) (rounded to bf16 once), so
+// K Q^T is the logit in log2 units.  ref is the reference point of the exponentials in those
+// units: every S^T accumulator STARTS at -ref, so the MFMA chain delivers logit - ref and P is
+// a bare exp2 of it.  ref is moved (and S, O, l rescaled) on the first step and afterwards only
+// when some row maximum outgrows it by more than kPairSlack; any reference gives the same O
+// after the final division by l.
+template <int D> struct PairState {
+    f32x16 o[D / 32];
+    bf16x8 qf[D / 16];
+    float ref, l_run;
+    bool started;
+};
+
+// LDS addresses of the wave's operand fragments inside a slot.  The XOR swizzle only touches
+// address bits 4-7 (K) / 4-6 (V^T), which the row offsets leave clear, so one base per operand
+// is enough: K fragment (key block c, channel step t) is at (k0 ^ (t << 5)) + c * 32 rows,
+// V^T fragment (channel block nb, key step kk of 16 slots) at (v0 ^ (kk << 5)) + nb * 4096.
+struct PairAddr {
+    uint32_t k0, v0;
+    int swap_addr;   // ds_bpermute address of lane ^ 32
+    int hh;
+};
+
+__device__ __forceinline__ float swap32(float x, int swap_addr) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(swap_addr, __builtin_bit_cast(int, x)));
+}
+
+// One key tile for one wave; slot = LDS byte offset of the (K tile, V^T tile) pair.
+// Issue order is pinned segment by segment (one MFMA each, scheduling barriers between): an
+// MFMA holds the matrix pipe for 32 cycles, a plain VALU op issues in 4 and exp2 in 8, so the
+// vector work placed in a segment runs in the MFMA's shadow.  LDS operand reads are issued
+// kAhead MFMAs before their consumer.
+template <int D>
+__device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, uint64_t vm, uint32_t slot) {
+    constexpr int G = D / 16, NB = D / 32, kAhead = 4;
+    constexpr int kRowB = D * 2;
+    constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
+    const uint32_t ka = fa.k0 + slot, va = fa.v0 + slot;
+    // Fragment f in issue order.  f < 2G: K fragment (c = f/G, t = f%G); then V^T fragments
+    // (kk = (f-2G)/NB, nb = (f-2G)%NB).
+#define VEDA_KF(f) lds_read16((ka ^ (uint32_t)(((f) % G) << 5)) + (uint32_t)(((f) / G) * 32 * kRowB))
+#define VEDA_VF(f) lds_read16((va ^ (uint32_t)(((f) / NB) << 5)) + (uint32_t)(((f) % NB) * 4096))
+#define VEDA_FRAG(f) ((f) < 2 * G ? VEDA_KF((f) < 2 * G ? (f) : 0) : VEDA_VF((f) < 2 * G ? 0 : (f) - 2 * G))
+    bf16x8 fr[NF];
+    bf16x8 pf[4];     // P^T operand of key step kk = 2c + s2: registers 8*s2..8*s2+7 of block c
+    f32x16 s[2];
+    const float init = -st.ref;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[c][i] = init;
+#pragma unroll
+    for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f);
+    __builtin_amdgcn_sched_barrier(0);
+    // S^T block 0
+#pragma unroll
+    for (int f = 0; f < G; ++f) {
+        fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], s[0], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // S^T block 1; the row maximum of block 0 rides along from the third MFMA on (block 0's
+    // last MFMA needs that long to retire)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int f = G; f < 2 * G; ++f) {
+        fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], s[1], 0, 0, 0);
+        if (f - G >= 2) {
+            constexpr int per = 16 / (G - 2) + (16 % (G - 2) ? 1 : 0);
+#pragma unroll
+            for (int e = 0; e < per; ++e) {
+                const int i = (f - G - 2) * per + e;
+                if (i < 16) mx = fmaxf(mx, s[0][i]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
+    if (vm != ~0ull) {
+        // Edge tile: padded key slots get -inf.  Register i of key block c is key slot
+        // 32c + 16*(i/8) + 8*hh + (i%8); the lane-dependent part is shifted out first so the
+        // per-register tests use constant bit positions.  The empty asm keeps this a real
+        // branch: if-converted into the main block it would cost ~90 vector ops on every step.
+        asm volatile("" ::: "memory");
+        mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * fa.hh);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (!((half >> (16 * (i >> 3) + (i & 7))) & 1u)) s[c][i] = -INFINITY;
+                mx = fmaxf(mx, s[c][i]);
+            }
+        }
+    }
+    mx = fmaxf(mx, swap32(mx, fa.swap_addr));   // row maximum relative to the reference
+    if (!st.started || __any(mx > kPairSlack)) {
+        // Move the reference of every row whose maximum is above it (first step: to the
+        // maximum itself, up or down).
+        float delta = st.started ? fmaxf(mx, 0.0f) : mx;
+        delta = delta == -INFINITY ? 0.0f : delta;
+        const float alpha = st.started ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // O = l = 0 before
+        st.ref += delta;
+        st.l_run *= alpha;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[c][i] -= delta;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st.o[nb][i] *= alpha;
+        st.started = true;
+    }
+    float psum = 0.0f;
+    // P^T of key step kk: exponentials of registers 8*(kk%2)..+7 of block kk/2
+    // two scores at a time, so that the pair is rounded to bf16 by one packed conversion
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+#define VEDA_EXP(kk, e)                                                                         \
+    do {                                                                                        \
+        const float p0_ = __builtin_amdgcn_exp2f(s[(kk) >> 1][8 * ((kk) & 1) + (e)]);           \
+        const float p1_ = __builtin_amdgcn_exp2f(s[(kk) >> 1][8 * ((kk) & 1) + (e) + 1]);       \
+        const bf16x2 pr_ = {(__bf16)p0_, (__bf16)p1_};                                          \
+        psum += p0_;                                                                            \
+        psum += p1_;                                                                            \
+        pf[kk][e] = pr_[0];                                                                     \
+        pf[kk][(e) + 1] = pr_[1];                                                               \
+    } while (0)
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) VEDA_EXP(0, e);
+    __builtin_amdgcn_sched_barrier(0);
+    // O^T += V^T P^T; the 8 exponentials of the next key step are spread over this key step's
+    // NB MFMAs
+#pragma unroll
+    for (int g = 0; g < 4 * NB; ++g) {
+        const int f = 2 * G + g;
+        if (f + kAhead < NF) fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+        const int kk = g / NB, nb = g % NB;
+        st.o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], pf[kk], st.o[nb], 0, 0, 0);
+        if (kk < 3) {
+#pragma unroll
+            for (int e = nb * (8 / NB); e < (nb + 1) * (8 / NB); e += 2) VEDA_EXP(kk + 1, e);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    st.l_run += psum;
+#undef VEDA_EXP
+#undef VEDA_FRAG
+#undef VEDA_KF
+#undef VEDA_VF
+}
+
+// After the last step: normalise, transpose through LDS and scatter the real rows of the
+// workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, lse_s after it.
+template <int D>
+__device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnArgs& a, const HeadGeom& hg, char* smem,
+                                            int head, int qiA, bool hasB, int64_t b, int tid, int which, int r,
+                                            int lq, int hh) {
+    constexpr int kRowB = D * 2, kKChunks = kRowB / 16;
+    const float l_all = st.l_run + __shfl_xor(st.l_run, 32);
+    const float inv = l_all > 0.0f ? 1.0f / l_all : 0.0f;
+    char* obuf = smem;
+    float* lse_s = reinterpret_cast<float*>(smem + 2 * kTile * kRowB);   // [2][64]
+    __syncthreads();
+    {
+        char* orow = obuf + (which * kTile + 32 * r + lq) * kRowB;
+#pragma unroll
+        for (int nb = 0; nb < D / 32; ++nb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int d0 = 32 * nb + 8 * j + 4 * hh;
+                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                bf16x4 pk;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) pk[t] = (__bf16)(st.o[nb][4 * j + t] * inv);
+                *reinterpret_cast<bf16x4*>(orow + d0 * 2) = pk;
+            }
+        if (hh == 0) lse_s[which * kTile + 32 * r + lq] = (st.ref + __log2f(l_all)) * kLn2;
+    }
+    __syncthreads();
+    char* ob = a.out + b * a.so_b + head * a.so_h;
+    const int n_tiles = hasB ? 2 : 1;
+    for (int cid = tid; cid < n_tiles * kTile * kKChunks; cid += 256) {
+        const int row = cid / kKChunks, ch = cid % kKChunks;
+        const int n = slot_token(hg, qiA + row / kTile, row % kTile, a.T, a.H, a.W);
+        if (n >= 0)
+            *reinterpret_cast<uint4*>(ob + (int64_t)n * a.so_n + ch * 16) =
+                *reinterpret_cast<const uint4*>(obuf + row * kRowB + ch * 16);
+    }
+    if (a.lse && tid < n_tiles * kTile) {
+        const int n = slot_token(hg, qiA + tid / kTile, tid % kTile, a.T, a.H, a.W);
+        if (n >= 0) a.lse[(b * a.n_heads + head) * a.tokens + n] = lse_s[tid];
+    }
+}
+
+// One step of the merged walk over the kept lists of the two query tiles of a workgroup.
+struct MergedStep {
+    int j;         // key tile (head-local)
+    int fl;        // bit 0: tile A keeps it, bit 1: tile B keeps it; 0 = past the end
+    uint64_t vm;   // validity mask of key tile j
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs a) {
+    constexpr int kRowB = D * 2;                 // bytes of one K row
+    constexpr int kKBytes = kTile * kRowB;       // K tile
+    constexpr int kVBytes = D * kTile * 2;       // V^T tile: D rows of 128 bytes
+    constexpr int kSlot = kKBytes + kVBytes;     // one LDS slot: K tile then V^T tile
+    constexpr int kKChunks = kRowB / 16;         // 16-byte chunks per K row
+    constexpr int kLoads = kKBytes / 1024 / 4;   // direct-load instructions per wave per tile (K; same for V)
+    constexpr int G = D / 16, NB = D / 32;
+    extern __shared__ __align__(1024) char smem[];   // base bits 4-9 clear: see PairAddr
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int which = wave >> 1, r = wave & 1;
+    const int lq = lane & 31, hh = lane >> 5;
+
+    int head, pair;
+    if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, 2, head, pair)) return;
+    const HeadGeom hg = a.heads[head];
+    const int64_t b = blockIdx.y;
+    const int qiA = 2 * pair;
+    const bool hasB = qiA + 1 < hg.n_tiles;
+    const int qi = (which == 0 || hasB) ? qiA + which : qiA;
+    const int64_t rowA = b * a.total_tiles + hg.tile_off + qiA;
+    const int begA = a.row_ptr[rowA], endA = a.row_ptr[rowA + 1];
+    const int nA = endA - begA;
+    const int nB = hasB ? a.row_ptr[rowA + 2] - endA : 0;
+    // The kept lists and the validity masks are read-only for the whole launch and indexed
+    // uniformly: reading them through the constant address space makes them scalar loads, so
+    // no vector-memory counter waits of the compiler's own end up inside the main loop.
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_t;
+    typedef const __attribute__((address_space(4))) uint64_t* const_u64_t;
+    const const_i32_t colsA = (const_i32_t)(uintptr_t)(a.col_idx + begA);
+    const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + (hasB ? endA : begA));
+    const const_u64_t vmask = (const_u64_t)(uintptr_t)(a.valid_mask + hg.tile_off);
+    const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
+    const char* kt = a.k + head_tile0 * kKBytes;
+    const char* vt = a.v + head_tile0 * kVBytes;
+
+    // Q operand (B matrix of S^T = K Q^T): lane holds query row 32r+lq, channels 16t+8hh..+8.
+    PairState<D> st;
+    {
+        const char* qrow = a.q + (head_tile0 + qi) * kKBytes + (32 * r + lq) * kRowB + 16 * hh;
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+            const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + 32 * t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.qf[t][e] = (__bf16)((float)raw[e] * a.scale_log2);
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.o[nb][i] = 0.0f;
+    st.ref = st.l_run = 0.0f;
+    st.started = false;
+
+    // global -> LDS copy plan.  One wave instruction fills 1 KB of LDS, lane i at byte 16*i, so
+    // the swizzle is applied on the global side: each lane fetches the chunk that belongs at
+    // its fixed LDS position.  Wave w issues instructions w*kLoads .. w*kLoads+kLoads-1 of each
+    // tile.
+    uint32_t k_src[kLoads], v_src[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+        const int inst = wave * kLoads + j;
+        const int krow = inst * (1024 / kRowB) + lane / kKChunks, kpos = lane % kKChunks;
+        k_src[j] = krow * kRowB + ((kpos ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
+        const int vrow = inst * 8 + (lane >> 3), vpos = lane & 7;
+        v_src[j] = vrow * 128 + ((vpos ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
+    }
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    const uint32_t wave_lds = smem_base + (uint32_t)wave * (kLoads * 1024);
+#define VEDA_LOAD_KV(j_tile, SLOT)                                                                         \
+    do {                                                                                                   \
+        const char* ksrc_ = kt + (int64_t)(j_tile) * kKBytes;                                              \
+        const char* vsrc_ = vt + (int64_t)(j_tile) * kVBytes;                                              \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
+            dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_, k_src[j]);                           \
+        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
+            dma16_to_lds(wave_lds + (SLOT) * kSlot + kKBytes + j * 1024, vsrc_, v_src[j]);                 \
+    } while (0)
+    // All of this wave's LDS-bound loads have landed (vmcnt 0), then meet the other waves.
+#define VEDA_LOADS_DONE_BARRIER()   \
+    do {                            \
+        wait_vmcnt<0>();            \
+        __syncthreads();            \
+    } while (0)
+
+    PairAddr fa;
+    fa.hh = hh;
+    fa.swap_addr = (lane ^ 32) << 2;
+    fa.k0 = smem_base + rho(lq) * kRowB + ((hh ^ (lq & (kKChunks - 1))) << 4);
+    fa.v0 = smem_base + kKBytes + lq * 128 + ((hh ^ (((lq >> 1) & 7) ^ ((lq & 1) << 2))) << 4);
+
+    // Merged walk: at every step take the smaller of the two list heads; a key tile kept by
+    // both query tiles is loaded once and used by both halves of the workgroup.  (Ascending
+    // lists, as stage 3 writes them, share the most; any order stays correct.)
+    // The list heads are kept as (raw loaded value, in-range flag) and only combined when the
+    // next step is formed, one step later: the scalar loads get a whole step to return.
+    constexpr int kEnd = 0x7fffffff;
+    int ia = 0, ib = 0;
+    int rawA = colsA[0], rawB = colsB[0];
+    bool okA = nA > 0, okB = nB > 0;
+#define VEDA_NEXT_STEP(e)                                                            \
+    do {                                                                             \
+        const int headA_ = okA ? rawA : kEnd, headB_ = okB ? rawB : kEnd;            \
+        const int j_ = headA_ < headB_ ? headA_ : headB_;                            \
+        const bool live_ = j_ != kEnd;                                               \
+        const int ta_ = (live_ && headA_ == j_) ? 1 : 0;                             \
+        const int tb_ = (live_ && headB_ == j_) ? 1 : 0;                             \
+        (e).j = live_ ? j_ : 0;                                                      \
+        (e).fl = ta_ | (tb_ << 1);                                                   \
+        (e).vm = vmask[(e).j];                                                       \
+        ia += ta_;                                                                   \
+        ib += tb_;                                                                   \
+        okA = ia < nA;                                                               \
+        okB = ib < nB;                                                               \
+        rawA = colsA[okA ? ia : 0];                                                  \
+        rawB = colsB[okB ? ib : 0];                                                  \
+    } while (0)
+
+    // Step s (P = s & 1) computes on slot P while the tiles of step s+1 land in slot P^1.
+    const int my_bit = 1 << which;
+    MergedStep e0, e1;
+    VEDA_NEXT_STEP(e0);
+    VEDA_NEXT_STEP(e1);
+    if (e0.fl) VEDA_LOAD_KV(e0.j, 0);
+    VEDA_LOADS_DONE_BARRIER();   // also the Q loads: nothing vector-memory is pending below
+
+#define VEDA_STEP(P)                                                                                     \
+    do {                                                                                                 \
+        if (e1.fl) VEDA_LOAD_KV(e1.j, (P) ^ 1);                                                          \
+        MergedStep e2;                                                                                   \
+        VEDA_NEXT_STEP(e2);                                                                              \
+        if (e0.fl & my_bit) pair_step<D>(st, fa, e0.vm, (uint32_t)((P) * kSlot));                        \
+        e0 = e1; e1 = e2;                                                                                \
+        VEDA_LOADS_DONE_BARRIER();                                                                       \
+    } while (0)
+    while (e0.fl) {
+        VEDA_STEP(0);
+        if (!e0.fl) break;
+        VEDA_STEP(1);
+    }
+#undef VEDA_STEP
+#undef VEDA_NEXT_STEP
+#undef VEDA_LOAD_KV
+#undef VEDA_LOADS_DONE_BARRIER
+
+    finish_pair<D>(st, a, hg, smem, head, qiA, hasB, b, tid, which, r, lq, hh);
+}
+
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, hipStream_t s) {
+    const int d = pl->prob.head_dim;
+    dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
+    const size_t smem = (size_t)2 * 2 * kTile * d * 2;   // two slots of (K tile + V^T tile)
+    if (d == 128) hipLaunchKernelGGL(sparse_attn_bf16_pair_kernel<128>, grid, block, smem, s, a);
+    else hipLaunchKernelGGL(sparse_attn_bf16_pair_kernel<64>, grid, block, smem, s, a);
+    return launch_status("sparse_attn_bf16_pair_kernel");
+}
+
+}  // namespace veda

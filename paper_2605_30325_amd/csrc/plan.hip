@@ -88,23 +88,33 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
         for (int32_t i = 0; i < (pl->heads[h].n_tiles + 63) / 64; ++i) row_blk.push_back((int32_t)((uint32_t)h << 24 | (uint32_t)i));
     pl->row_blocks = (int64_t)row_blk.size();
 
-    std::vector<int32_t> xcd_cum((size_t)veda::kXcd * (p->heads + 1), 0);
-    for (int x = 0; x < veda::kXcd; ++x) {
-        int32_t acc = 0;
-        for (int h = 0; h < p->heads; ++h) {
-            xcd_cum[(size_t)x * (p->heads + 1) + h] = acc;
-            const int32_t n = pl->heads[h].n_tiles;
-            acc += n / veda::kXcd + (x < n % veda::kXcd ? 1 : 0);
+    // unit = 1: query tiles; unit = 2: pairs of adjacent query tiles
+    auto die_split = [&](int unit, int32_t& max_total) {
+        std::vector<int32_t> cum((size_t)veda::kXcd * (p->heads + 1), 0);
+        for (int x = 0; x < veda::kXcd; ++x) {
+            int32_t acc = 0;
+            for (int h = 0; h < p->heads; ++h) {
+                cum[(size_t)x * (p->heads + 1) + h] = acc;
+                const int32_t n = (pl->heads[h].n_tiles + unit - 1) / unit;
+                acc += n / veda::kXcd + (x < n % veda::kXcd ? 1 : 0);
+            }
+            cum[(size_t)x * (p->heads + 1) + p->heads] = acc;
+            max_total = acc > max_total ? acc : max_total;
         }
-        xcd_cum[(size_t)x * (p->heads + 1) + p->heads] = acc;
-        pl->xcd_max_tiles = acc > pl->xcd_max_tiles ? acc : pl->xcd_max_tiles;
-    }
+        return cum;
+    };
+    const std::vector<int32_t> xcd_cum = die_split(1, pl->xcd_max_tiles);
+    const std::vector<int32_t> xcd_cum_pair = die_split(2, pl->xcd_max_pairs);
 
     hipError_t e = hipGetDevice(&pl->device);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum, xcd_cum.size() * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_row_blk, row_blk.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum_pair, xcd_cum_pair.size() * sizeof(int32_t));
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_xcd_cum_pair, xcd_cum_pair.data(), xcd_cum_pair.size() * sizeof(int32_t),
+                      hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipMemcpy(pl->d_row_blk, row_blk.data(), row_blk.size() * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess)
@@ -128,6 +138,7 @@ void veda_plan_destroy(veda_plan* pl) {
     if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
     if (pl->d_xcd_cum) (void)hipFree(pl->d_xcd_cum);
     if (pl->d_row_blk) (void)hipFree(pl->d_row_blk);
+    if (pl->d_xcd_cum_pair) (void)hipFree(pl->d_xcd_cum_pair);
     delete pl;
 }
 

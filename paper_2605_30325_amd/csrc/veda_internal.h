@@ -59,6 +59,9 @@ struct veda_plan {
     // d_xcd_cum[x*(heads+1) + h] = number of query tiles die x owns in heads < h.
     int32_t* d_xcd_cum = nullptr;       // device [8][heads+1]
     int32_t xcd_max_tiles = 0;          // max over dies of the die's total
+    // The same split over PAIRS of adjacent query tiles (2p, 2p+1), for the pair kernel.
+    int32_t* d_xcd_cum_pair = nullptr;  // device [8][heads+1]
+    int32_t xcd_max_pairs = 0;
     int elem_size() const { return prob.dtype == VEDA_BF16 ? 2 : 4; }
     int64_t tokens() const { return (int64_t)prob.T * prob.H * prob.W; }
 };
