@@ -124,6 +124,59 @@ def test_row_stochastic_weights_on_gpu():
     assert (out.float() - 1.0).abs().max().item() <= 2 ** -7
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64)])
+def test_attention_on_hand_made_lists(dtype, d):
+    # Stage 4 alone on kept lists that stage 3 would never write: unsorted, neighbours with
+    # identical / disjoint / partly shared lists.  The grid gives every head an odd tile count
+    # (the last query tile has no neighbour) and ragged tiles on every axis.
+    wl = wlm.custom_workload(f"lists_{dtype}_{d}", 3, d, dtype, (9, 18, 18), True, (25, 100), seed=31)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, v = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    assert all(n % 2 for n in plan.tiles)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, want_mask=False)
+    rng = np.random.default_rng(31)
+    ksel = 7
+    sels, cols = [], []
+    for h in range(wl.heads):
+        n = plan.tiles[h]
+        sel = np.stack([rng.choice(n, ksel, replace=False) for _ in range(n)]).astype(np.int32)   # unsorted
+        for i in range(0, n - 1, 2):
+            kind = (i // 2) % 4
+            if kind == 0:
+                sel[i + 1] = sel[i][::-1]                                   # same tiles, other order
+            elif kind == 1:
+                rest = np.setdiff1d(np.arange(n), sel[i])
+                sel[i + 1] = rng.choice(rest, ksel, replace=False)          # nothing shared
+            elif kind == 2:
+                sel[i], sel[i + 1] = np.sort(sel[i]), np.sort(sel[i + 1])   # ascending, as stage 3 writes
+        sels.append(sel)
+        cols.append(sel.reshape(-1))
+    col_idx = torch.as_tensor(np.concatenate(cols)).to(dev)
+    row_ptr = torch.arange(plan.total_tiles + 1, dtype=torch.int32, device=dev) * ksel
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((1, wl.heads, wl.tokens, d), float("nan"), dtype=wl.torch_dtype, device=dev)
+    out, lse = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, row_ptr, col_idx, scale, out=out, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    queries = np.arange(wl.tokens)
+    for h in range(wl.heads):
+        shape = tuple(int(x) for x in shapes[h])
+        ref, lse_ref, _ = vo.masked_attention(hz.to_f32_numpy(q[0, h]), hz.to_f32_numpy(k[0, h]),
+                                              hz.to_f32_numpy(v[0, h]), wl.grid, shape, sels[h], scale, queries,
+                                              want_stats=True)
+        err = np.abs(hz.to_f32_numpy(out[0, h]).astype(np.float64) - ref)
+        lerr = np.abs(lse[0, h].cpu().numpy().astype(np.float64) - lse_ref)
+        _say(f"[parity] {wl.name} head {h} {shape}: max_abs {err.max():.2e} mean_abs {err.mean():.2e} lse {lerr.max():.2e}")
+        if dtype == "bf16":
+            assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS and lerr.max() <= 2e-2
+        else:
+            assert err.max() <= hz.F32_MAX_ABS and lerr.max() <= 1e-4
+
+
 def test_select_on_constructed_ties_and_special_values():
     wl = wlm.custom_workload("ties", 2, 64, "f32", (4, 8, 40), False, (1, 4), seed=15, latent_dim=32)
     shapes = wlm.tile_shapes(wl)
