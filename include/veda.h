@@ -71,7 +71,7 @@ typedef struct { int64_t b, h, n; } veda_strides;
  *   w2 [heads][hidden][out_dim],                    b2 [heads][out_dim].                   */
 typedef struct {
     int32_t in_dim;   /* must be 3*head_dim (Avg|Max|Min)          */
-    int32_t hidden;   /* 0 or 1..1024                               */
+    int32_t hidden;   /* 0 or 1..512                                */
     int32_t out_dim;  /* latent size d', 1..256, multiple of 4      */
     veda_act act;
     const float *w1, *b1, *w2, *b2;
@@ -129,14 +129,16 @@ veda_status veda_tile_select(const veda_plan*, const float* scores, const int32_
 
 /* ---- stage 4: block-sparse flash attention + un-tiling (Eq. 2; Sec. 4.3; Alg. 1 "UnTile") -- */
 /* q_tiled,k_tiled  VEDA_TOKEN_MAJOR; v_tiled VEDA_CHANNEL_MAJOR; valid_mask from stage 1.
- * row_ptr/col_idx  CSR lists as written by stage 3 (any order within a row is accepted;
- *                  every row needs at least one entry, indices in [0, N_T[h])).
+ * row_ptr/col_idx  CSR lists as written by stage 3 (any order within a row is accepted, no
+ *                  index twice in a row; every row needs at least one entry, indices in
+ *                  [0, N_T[h]); ascending rows let adjacent query tiles share loads).
  * out      device, token order, strides so, plan dtype: for every real query token u of
  *          query tile i, O[u] = softmax over the real tokens of the kept key tiles of
  *          (q_u.k_v * softmax_scale) applied to V.  Padded query slots write nothing.
  * lse      optional device fp32 [batch][heads][N]: natural-log sum of exp of the kept logits.
- * bf16: Q K^T and P V run on bf16 MFMA with fp32 accumulation, softmax in fp32, P rounded
- * to bf16 before P V.  f32: fp32 arithmetic throughout. */
+ * bf16: Q K^T and P V run on bf16 MFMA with fp32 accumulation, softmax in fp32; Q is scaled
+ * by softmax_scale*log2(e) and rounded to bf16 once, P is rounded to bf16 before P V.
+ * f32: fp32 arithmetic throughout. */
 veda_status veda_sparse_attn_fwd(const veda_plan*, const void* q_tiled, const void* k_tiled,
                                  const void* v_tiled, const uint64_t* valid_mask,
                                  const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
