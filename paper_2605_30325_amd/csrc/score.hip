@@ -97,22 +97,29 @@ struct MlpDev {
 
 constexpr int kMlpRows = 64;       // tiles per workgroup
 constexpr int kMlpCols = 128;      // output units per pass
-constexpr int kMlpK = 32;          // reduction indices staged per step
+constexpr int kMlpK = 16;          // reduction indices staged per step
 constexpr int kMlpThreads = 256;
 constexpr int kMlpXPitch = kMlpK + 4;   // floats; keeps every staged row 16-byte aligned
+constexpr int kMlpWsFloats = kMlpK * kMlpCols;        // one weight stage
+constexpr int kMlpXsFloats = kMlpRows * kMlpXPitch;   // one input stage
 
 // One affine layer for the 64 rows of a workgroup:
 //   out[r][n] = act(bias[n] + sum_k x[r][k] * w[k][n]),  one fmaf chain per (r,n), k ascending.
 // Thread (rg = tid/32, jg = tid%32) keeps rows 8*rg..+7 x outputs c0+4*jg..+3 in registers.  The
-// weights of 32 reduction indices x 128 outputs are staged in LDS per step (ws); the inputs come
-// either from global memory, staged alongside (xs), or from a resident LDS array (x_lds).
-// Results go to an LDS array (y_lds, pitch ldy) or to global rows (y_glb, pitch N).
+// weights of 16 reduction indices x 128 outputs are staged in LDS per step (ws, two buffers);
+// the inputs come either from global memory, staged alongside (xs, two buffers), or from a
+// resident LDS array (x_lds).  The global loads of step s+1 are in flight while step s is
+// computed; one barrier per step.  Results go to an LDS array (y_lds, pitch ldy) or to global
+// rows (y_glb, pitch N).
 template <bool kXGlobal, bool kYLds>
 __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const float* x_lds, int ldx, int rows,
                                           int K, const float* __restrict__ w, const float* __restrict__ bias,
                                           int N, bool relu, float* y_lds, int ldy, float* __restrict__ y_glb,
                                           float* xs, float* ws) {
+    constexpr int kWPer = kMlpWsFloats / kMlpThreads;   // staged weights per thread and step (8)
+    static_assert(kMlpRows * (kMlpK / 4) == kMlpThreads, "one float4 of the inputs per thread and step");
     const int jg = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int xr = threadIdx.x / (kMlpK / 4), xi = (threadIdx.x % (kMlpK / 4)) * 4;   // staged input float4
     for (int c0 = 0; c0 < N; c0 += kMlpCols) {
         float acc[8][4];
 #pragma unroll
@@ -122,29 +129,42 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
 #pragma unroll
             for (int r = 0; r < 8; ++r) acc[r][e] = bv;
         }
-        for (int k0 = 0; k0 < K; k0 += kMlpK) {
+        float wreg[kWPer];
+        float4 xreg = make_float4(0.f, 0.f, 0.f, 0.f);
+        auto fetch = [&](int k0) {
             const int kc = K - k0 < kMlpK ? K - k0 : kMlpK;
-            __syncthreads();
-            for (int t = threadIdx.x; t < kMlpK * kMlpCols; t += kMlpThreads) {
-                const int i = t / kMlpCols, c = t % kMlpCols;
-                ws[t] = (i < kc && c0 + c < N) ? w[(int64_t)(k0 + i) * N + c0 + c] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < kWPer; ++u) {
+                const int t = threadIdx.x + u * kMlpThreads, i = t / kMlpCols, c = t % kMlpCols;
+                wreg[u] = (i < kc && c0 + c < N) ? w[(int64_t)(k0 + i) * N + c0 + c] : 0.0f;
             }
-            if (kXGlobal) {
-                for (int t = threadIdx.x; t < kMlpRows * (kMlpK / 4); t += kMlpThreads) {
-                    const int r = t / (kMlpK / 4), i4 = (t % (kMlpK / 4)) * 4;   // K is a multiple of 4 here
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (r < rows && i4 < kc) v = *reinterpret_cast<const float4*>(x_glb + (int64_t)r * K + k0 + i4);
-                    *reinterpret_cast<float4*>(xs + r * kMlpXPitch + i4) = v;
-                }
+            if (kXGlobal) {   // K is a multiple of 4 here
+                xreg = (xr < rows && xi < kc) ? *reinterpret_cast<const float4*>(x_glb + (int64_t)xr * K + k0 + xi)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            __syncthreads();
-            const float* xb = kXGlobal ? xs + (8 * rg) * kMlpXPitch : x_lds + (8 * rg) * ldx + k0;
+        };
+        auto stash = [&](int buf) {
+#pragma unroll
+            for (int u = 0; u < kWPer; ++u) ws[buf * kMlpWsFloats + threadIdx.x + u * kMlpThreads] = wreg[u];
+            if (kXGlobal) *reinterpret_cast<float4*>(xs + buf * kMlpXsFloats + xr * kMlpXPitch + xi) = xreg;
+        };
+        __syncthreads();   // the previous pass (or layer) is done with both stages
+        fetch(0);
+        stash(0);
+        __syncthreads();
+        int buf = 0;
+        for (int k0 = 0; k0 < K; k0 += kMlpK, buf ^= 1) {
+            const int kc = K - k0 < kMlpK ? K - k0 : kMlpK;
+            const bool more = k0 + kMlpK < K;
+            if (more) fetch(k0 + kMlpK);
+            const float* wb = ws + buf * kMlpWsFloats;
+            const float* xb = kXGlobal ? xs + buf * kMlpXsFloats + (8 * rg) * kMlpXPitch : x_lds + (8 * rg) * ldx + k0;
             const int xp = kXGlobal ? kMlpXPitch : ldx;
             int kk = 0;
             for (; kk + 4 <= kc; kk += 4) {
                 float4 wv[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) wv[e] = *reinterpret_cast<const float4*>(ws + (kk + e) * kMlpCols + 4 * jg);
+                for (int e = 0; e < 4; ++e) wv[e] = *reinterpret_cast<const float4*>(wb + (kk + e) * kMlpCols + 4 * jg);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
                     const float4 xv = *reinterpret_cast<const float4*>(xb + r * xp + kk);
@@ -167,7 +187,7 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
                 }
             }
             for (; kk < kc; ++kk) {   // tail of a reduction length that is not a multiple of 4
-                const float4 wv = *reinterpret_cast<const float4*>(ws + kk * kMlpCols + 4 * jg);
+                const float4 wv = *reinterpret_cast<const float4*>(wb + kk * kMlpCols + 4 * jg);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
                     const float xv = xb[r * xp + kk];
@@ -177,6 +197,8 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
                     acc[r][3] = __builtin_fmaf(xv, wv.w, acc[r][3]);
                 }
             }
+            if (more) stash(buf ^ 1);
+            __syncthreads();
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -197,7 +219,7 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
 // One workgroup projects up to 64 consecutive tiles of one head (Eq. 5, phi_q or phi_k).
 // row_blk[x] = head << 24 | index of the 64-tile block inside that head.
 // grid = (row blocks of all heads, 2 estimators, batch); dynamic LDS = staging + hidden layer.
-__global__ __launch_bounds__(kMlpThreads) void mlp_kernel(const HeadGeom* __restrict__ heads,
+__global__ __launch_bounds__(kMlpThreads, 4) void mlp_kernel(const HeadGeom* __restrict__ heads,
                                                          const int32_t* __restrict__ row_blk,
                                                          const float* __restrict__ zq, const float* __restrict__ zk,
                                                          float* __restrict__ yq, float* __restrict__ yk,
@@ -206,9 +228,9 @@ __global__ __launch_bounds__(kMlpThreads) void mlp_kernel(const HeadGeom* __rest
     const MlpDev p = blockIdx.y == 0 ? pq : pk;
     const float* z = blockIdx.y == 0 ? zq : zk;
     float* y = blockIdx.y == 0 ? yq : yk;
-    float* ws = smem;                                   // [32][128]
-    float* xs = ws + kMlpK * kMlpCols;                  // [64][36]
-    float* hs = xs + kMlpRows * kMlpXPitch;             // [64][ldh]
+    float* ws = smem;                                   // 2 x [16][128]
+    float* xs = ws + 2 * kMlpWsFloats;                  // 2 x [64][20]
+    float* hs = xs + 2 * kMlpXsFloats;                  // [64][ldh]
     const int32_t code = row_blk[blockIdx.x];
     const int head = code >> 24, blk = code & 0xffffff;
     const HeadGeom hg = heads[head];
@@ -362,7 +384,7 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
     MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
     const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
-    const size_t smem = sizeof(float) * ((size_t)kMlpK * kMlpCols + (size_t)kMlpRows * kMlpXPitch +
+    const size_t smem = sizeof(float) * ((size_t)2 * kMlpWsFloats + (size_t)2 * kMlpXsFloats +
                                          (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3));
     if (smem > 64 * 1024)
         VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
