@@ -176,7 +176,7 @@ def main():
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
         "attn_kept_tflops": kept_tflops,
         "stage_ms": stage_ms,
-        "roofline": {"kernel": "sparse_attn_bf16_kernel" if wl.dtype == "bf16" else "sparse_attn_f32_kernel",
+        "roofline": {"kernel": "sparse_attn_bf16_pair_kernel" if wl.dtype == "bf16" else "sparse_attn_f32_kernel",
                      "bound": "mfma" if wl.dtype == "bf16" else "alu",
                      "achieved": kept_tflops,
                      "peak": PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS,

@@ -177,6 +177,19 @@ def test_attention_on_hand_made_lists(dtype, d):
             assert err.max() <= hz.F32_MAX_ABS and lerr.max() <= 1e-4
 
 
+def test_maximum_head_count():
+    # 128 heads (the library's limit) on a small ragged grid: per-head tables, the die-aware work
+    # split and the 64-tile projection blocks all see many short heads
+    wl = wlm.custom_workload("heads128", 128, 64, "bf16", (5, 6, 10), True, (50, 100), seed=41, latent_dim=16)
+    run = hz.run_gpu_path(wl)
+    assert torch.isfinite(run.out.float()).all()
+    for h in (0, 1, 63, 126, 127):
+        st = hz.check_head(run, h)
+        _say(f"[parity] {wl.name} h{h} {tuple(run.shapes[h])}: {st}")
+    with pytest.raises(veda.VedaError):
+        veda.Plan(1, 129, 64, wl.grid, np.tile(np.asarray([[4, 4, 4]], np.int32), (129, 1)), torch.bfloat16)
+
+
 def test_select_on_constructed_ties_and_special_values():
     wl = wlm.custom_workload("ties", 2, 64, "f32", (4, 8, 40), False, (1, 4), seed=15, latent_dim=32)
     shapes = wlm.tile_shapes(wl)
