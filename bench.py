@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--dense", action="store_true", help="also time one dense (k = N_T) attention call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
+    ap.add_argument("--unfused", action="store_true",
+                    help="stage 2 re-reads the tiled Q and K for its descriptors (veda_tile_layout + veda_tile_score) "
+                         "instead of taking them during the gathers")
     return ap.parse_args()
 
 
@@ -115,7 +118,12 @@ def main():
     dense_flops = 4.0 * N * N * d * heads * wl.batch
     slots = int(tiles.sum()) * 64 * wl.batch
     bytes_layout = 3 * (N * heads * wl.batch * d * es + slots * d * es)
-    bytes_score = 2 * slots * d * es + int((tiles * tiles).sum()) * 4 * wl.batch
+    stat_bytes = 2 * int(tiles.sum()) * wl.batch * 3 * d * 4     # descriptors of Q and K tiles
+    if args.unfused:
+        bytes_score = 2 * slots * d * es + int((tiles * tiles).sum()) * 4 * wl.batch
+    else:   # the gathers also write the descriptors; the score stage reads them instead of the tiles
+        bytes_layout += stat_bytes
+        bytes_score = stat_bytes + int((tiles * tiles).sum()) * 4 * wl.batch
     bytes_select = int((tiles * tiles).sum()) * 4 * wl.batch + pairs * 4
     bytes_attn_kv = pairs * 2 * 64 * d * es
 
@@ -125,11 +133,19 @@ def main():
     def step(events=None):
         ev = events
         if ev: ev[0].record()
-        qt, vm, vc = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
-        kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
+        if args.unfused:
+            qt, vm, vc = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
+            kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
+        else:   # TripPool descriptors taken during the Q and K gathers
+            qt, vm, vc, zq = veda.veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"), bufs.get("zq"))
+            kt, _, _, zk = veda.veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False)
+            bufs.update(zq=zq, zk=zk)
         vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
         if ev: ev[1].record()
-        s, ws = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
+        if args.unfused:
+            s, ws = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
+        else:
+            s, ws = veda.veda_tile_score_stats(plan, zq, zk, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
         if ev: ev[2].record()
         rp, ci = veda.veda_tile_select(plan, s, kph, bufs.get("rp"), bufs.get("ci"))
         if ev: ev[3].record()

@@ -116,6 +116,20 @@ veda_status veda_tile_score(const veda_plan*, const void* q_tiled, const void* k
                             float scale, float* scores, void* workspace, size_t workspace_bytes,
                             void* stream);
 
+/* ---- stages 1 + 2 with the descriptors taken during the gather (Eq. 4; the Conclusion
+ * names tighter fusion of mask preparation as the next step for the kernels) --------------- */
+/* veda_tile_layout_stats = veda_tile_layout(VEDA_TOKEN_MAJOR) that also writes
+ * stats   device fp32 [batch][total_tiles][3*head_dim] = [Avg|Max|Min] of every tile over its
+ *         real tokens, per channel, bit-identical to the descriptors veda_tile_score derives.
+ * veda_tile_score_stats = veda_tile_score starting from such descriptors (stats_q of Q, stats_k
+ * of K); workspace needs batch*total_tiles*2*out_dim floats (veda_plan_workspace_bytes() is
+ * enough).  scores are bit-identical to veda_tile_score on the same inputs. */
+veda_status veda_tile_layout_stats(const veda_plan*, const void* x, veda_strides sx, void* x_tiled,
+                                   uint64_t* valid_mask, int32_t* valid_cnt, float* stats, void* stream);
+veda_status veda_tile_score_stats(const veda_plan*, const float* stats_q, const float* stats_k,
+                                  const veda_mlp* phi_q, const veda_mlp* phi_k, float scale, float* scores,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- stage 3: per-query-tile top-k (Sec. 3.1 "exactly k per row"; Sec. 4.1; Alg. 2) ------ */
 /* scores      device, as written by stage 2.
  * k_per_head  host i32 [heads], 1 <= k[h] <= N_T[h].

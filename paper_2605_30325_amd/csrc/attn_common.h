@@ -60,12 +60,12 @@ __device__ inline int rho(int m) {  // swap bits 2 and 3
 // lds_base + 16*i (lds_base wave-uniform), from global address base + voff (base uniform).
 // Written as inline assembly so that the compiler does not serialise later LDS reads of OTHER
 // buffers behind these loads; completion is awaited explicitly (vmcnt) before the barrier that
-// publishes the buffer.  M0 carries the LDS base and is dead outside the statement.
+// publishes the buffer.  M0 carries the LDS base (declared clobbered).
 __device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voff), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Launches the query-tile-pair bf16 kernel (attn_pair.hip); a.xcd_cum must be the pair table.

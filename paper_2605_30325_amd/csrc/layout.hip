@@ -91,6 +91,81 @@ __global__ __launch_bounds__(256) void layout_channel_major_kernel(
     }
 }
 
+// Token-major tiling with the TripPool descriptors (Eq. 4: Avg | Max | Min over the tile's real
+// tokens, per channel) taken on the way, so the tiled tensor is not read back for them.
+// One thread owns 16 bytes of the channel axis of one tile and walks its 64 slots in order:
+// the sum is the same slot-ascending fp32 chain the scoring stage uses, so the descriptors are
+// bit-identical to the ones it derives from the tiled tensor.  A workgroup holds 256 / (D / kN)
+// consecutive global tiles (they may belong to different heads).
+#pragma clang fp contract(off)
+template <typename E, int D>
+__global__ __launch_bounds__(256) void layout_stats_kernel(
+    const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
+    const char* __restrict__ x, int64_t sb, int64_t sh, int64_t sn, char* __restrict__ out,
+    float* __restrict__ stats, int64_t total_tiles, int T, int H, int W,
+    uint64_t* __restrict__ valid_mask, int32_t* __restrict__ valid_cnt, RecipTable recip) {
+    constexpr int kN = Chunk<E>::kN;
+    constexpr int kTpt = D / kN;            // threads per tile
+    constexpr int kTiles = 256 / kTpt;      // tiles per workgroup
+    constexpr int kRowBytes = D * (int)sizeof(E);
+    __shared__ int tok[kTiles][kTile];
+    const int64_t g0 = (int64_t)blockIdx.x * kTiles;
+    const int b = blockIdx.y;
+    for (int e = threadIdx.x; e < kTiles * kTile; e += 256) {
+        const int tl = e / kTile, l = e % kTile;
+        const int64_t g = g0 + tl;
+        int n = -1;
+        if (g < total_tiles) {
+            const HeadGeom hg = heads[tile_head[g]];
+            n = slot_token(hg, (int)(g - hg.tile_off), l, T, H, W);
+        }
+        tok[tl][l] = n;
+    }
+    __syncthreads();
+    const int tl = threadIdx.x / kTpt, chunk = threadIdx.x % kTpt;
+    const int64_t g = g0 + tl;
+    if (g >= total_tiles) return;
+    const int head = tile_head[g];
+    const char* xb = x + b * sb + head * sh + chunk * 16;
+    const int64_t row = (int64_t)b * total_tiles + g;
+    char* ob = out + row * (int64_t)kTile * kRowBytes + chunk * 16;
+    float sum[kN], mx[kN], mn[kN];
+#pragma unroll
+    for (int j = 0; j < kN; ++j) { sum[j] = 0.0f; mx[j] = -INFINITY; mn[j] = INFINITY; }
+    uint64_t mask = 0ull;
+#pragma unroll 8
+    for (int l = 0; l < kTile; ++l) {
+        const int n = tok[tl][l];
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n >= 0) {
+            v = *reinterpret_cast<const uint4*>(xb + (int64_t)n * sn);
+            mask |= 1ull << l;
+            float f[kN];
+            Chunk<E>::unpack(v, f);
+#pragma unroll
+            for (int j = 0; j < kN; ++j) {
+                sum[j] = sum[j] + f[j];
+                mx[j] = f[j] > mx[j] ? f[j] : mx[j];
+                mn[j] = f[j] < mn[j] ? f[j] : mn[j];
+            }
+        }
+        *reinterpret_cast<uint4*>(ob + l * kRowBytes) = v;
+    }
+    const int cnt = __popcll(mask);
+    const float inv = recip.v[cnt];
+    float* z = stats + row * (3 * D) + chunk * kN;
+#pragma unroll
+    for (int j = 0; j < kN; ++j) {
+        z[j] = sum[j] * inv;
+        z[D + j] = mx[j];
+        z[2 * D + j] = mn[j];
+    }
+    if (chunk == 0 && b == 0) {
+        if (valid_mask) valid_mask[g] = mask;
+        if (valid_cnt) valid_cnt[g] = cnt;
+    }
+}
+
 }  // namespace veda
 
 extern "C" veda_status veda_tile_layout(const veda_plan* pl, const void* x, veda_strides sx,
@@ -124,4 +199,37 @@ extern "C" veda_status veda_tile_layout(const veda_plan* pl, const void* x, veda
 #undef VEDA_LAUNCH_CM
     }
     return launch_status("veda_tile_layout");
+}
+
+extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x, veda_strides sx, void* x_tiled,
+                                              uint64_t* valid_mask, int32_t* valid_cnt, float* stats,
+                                              void* stream) {
+    using namespace veda;
+    if (!pl || !x || !x_tiled || !stats) return VEDA_ERR_INVALID_ARG;
+    const int es = pl->elem_size();
+    const int d = pl->prob.head_dim;
+    if (sx.n < d || sx.b < 0 || sx.h < 0) return VEDA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(x_tiled) || !aligned16(stats) || (sx.b * es) % 16 || (sx.h * es) % 16 ||
+        (sx.n * es) % 16)
+        return VEDA_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t sb = sx.b * es, sh = sx.h * es, sn = sx.n * es;
+    const int T = pl->prob.T, H = pl->prob.H, W = pl->prob.W;
+    RecipTable recip;
+    recip.v[0] = 0.0f;
+    for (int c = 1; c <= kTile; ++c) recip.v[c] = 1.0f / (float)c;
+#define VEDA_LAUNCH_LS(E, D)                                                                              \
+    do {                                                                                                  \
+        constexpr int tiles = 256 / (D / Chunk<E>::kN);                                                   \
+        dim3 grid((unsigned)((pl->total_tiles + tiles - 1) / tiles), (unsigned)pl->prob.batch);           \
+        hipLaunchKernelGGL((layout_stats_kernel<E, D>), grid, dim3(256), 0, st, pl->d_heads,              \
+                           pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, stats,            \
+                           pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                       \
+    } while (0)
+    if (es == 2 && d == 128) VEDA_LAUNCH_LS(uint16_t, 128);
+    else if (es == 2 && d == 64) VEDA_LAUNCH_LS(uint16_t, 64);
+    else if (es == 4 && d == 128) VEDA_LAUNCH_LS(uint32_t, 128);
+    else VEDA_LAUNCH_LS(uint32_t, 64);
+#undef VEDA_LAUNCH_LS
+    return launch_status("veda_tile_layout_stats");
 }

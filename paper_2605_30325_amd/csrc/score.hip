@@ -14,28 +14,6 @@
 
 namespace veda {
 
-struct RecipTable { float v[kTile + 1]; };  // v[c] = 1.0f / (float)c, computed on the host
-
-template <typename E> struct Chunk;
-template <> struct Chunk<uint16_t> {  // bf16: 8 channels per 16 bytes
-    static constexpr int kN = 8;
-    __device__ static void unpack(const uint4& u, float* f) {
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f[2 * j] = __uint_as_float(w[j] << 16);
-            f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
-        }
-    }
-};
-template <> struct Chunk<uint32_t> {  // fp32: 4 channels per 16 bytes
-    static constexpr int kN = 4;
-    __device__ static void unpack(const uint4& u, float* f) {
-        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
-        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
-    }
-};
-
 // One thread owns kN channels of one tile and walks its 64 slots in order.
 // grid = (ceil(rows / tiles_per_block), 2 tensors); rows = batch * total_tiles.
 template <typename E, int D>
@@ -338,6 +316,37 @@ static veda_status check_mlp(const veda_plan* pl, const veda_mlp* m) {
     return VEDA_OK;
 }
 
+// Projections (Eq. 5 phi_q, phi_k) of the descriptors zq, zk into yq, yk, then the score blocks.
+static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
+                                     const float* zq, const float* zk, float* yq, float* yk, float* scores,
+                                     hipStream_t s) {
+    const int dp = phi_q->out_dim;
+    const int64_t total = pl->total_tiles;
+    veda_status st;
+    MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
+    MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
+    const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
+    const size_t smem = sizeof(float) * ((size_t)2 * kMlpWsFloats + (size_t)2 * kMlpXsFloats +
+                                         (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3));
+    if (smem > 64 * 1024)
+        VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    dim3 mgrid((unsigned)pl->row_blocks, 2, (unsigned)pl->prob.batch);
+    hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_row_blk, zq, zk, yq,
+                       yk, pq, pk, total);
+    st = launch_status("mlp_kernel");
+    if (st != VEDA_OK) return st;
+
+    dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
+    hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, dp,
+                       scale, total, pl->score_elems);
+    return launch_status("score_kernel");
+}
+
+static void fill_recip(RecipTable& recip) {
+    recip.v[0] = 0.0f;
+    for (int c = 1; c <= kTile; ++c) recip.v[c] = 1.0f / (float)c;
+}
+
 }  // namespace veda
 
 extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
@@ -362,8 +371,7 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     hipStream_t s = (hipStream_t)stream;
 
     RecipTable recip;
-    recip.v[0] = 0.0f;
-    for (int c = 1; c <= kTile; ++c) recip.v[c] = 1.0f / (float)c;
+    fill_recip(recip);
 
     const bool bf16 = pl->prob.dtype == VEDA_BF16;
 #define VEDA_LAUNCH_TP(E, D)                                                                               \
@@ -381,21 +389,24 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     st = launch_status("trippool_kernel");
     if (st != VEDA_OK) return st;
 
-    MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
-    MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
-    const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
-    const size_t smem = sizeof(float) * ((size_t)2 * kMlpWsFloats + (size_t)2 * kMlpXsFloats +
-                                         (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3));
-    if (smem > 64 * 1024)
-        VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    dim3 mgrid((unsigned)pl->row_blocks, 2, (unsigned)pl->prob.batch);
-    hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_row_blk, zq, zk, yq,
-                       yk, pq, pk, total);
-    st = launch_status("mlp_kernel");
-    if (st != VEDA_OK) return st;
+    return project_and_score(pl, phi_q, phi_k, scale, zq, zk, yq, yk, scores, s);
+}
 
-    dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
-    hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, dp,
-                       scale, total, pl->score_elems);
-    return launch_status("score_kernel");
+extern "C" veda_status veda_tile_score_stats(const veda_plan* pl, const float* stats_q, const float* stats_k,
+                                             const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
+                                             float* scores, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+    using namespace veda;
+    if (!pl || !stats_q || !stats_k || !scores) return VEDA_ERR_INVALID_ARG;
+    veda_status st = check_mlp(pl, phi_q);
+    if (st == VEDA_OK) st = check_mlp(pl, phi_k);
+    if (st != VEDA_OK) return st;
+    if (phi_q->out_dim != phi_k->out_dim) return VEDA_ERR_INVALID_ARG;
+    if (!aligned16(stats_q) || !aligned16(stats_k) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
+    const int64_t rows = pl->total_tiles * pl->prob.batch;
+    const int dp = phi_q->out_dim;
+    if (!workspace || workspace_bytes < sizeof(float) * (size_t)rows * 2 * (size_t)dp) return VEDA_ERR_WORKSPACE;
+    float* yq = (float*)workspace;
+    float* yk = yq + rows * dp;
+    return project_and_score(pl, phi_q, phi_k, scale, stats_q, stats_k, yq, yk, scores, (hipStream_t)stream);
 }

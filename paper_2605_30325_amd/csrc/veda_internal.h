@@ -28,6 +28,28 @@ struct HeadGeom {
 };
 
 #if defined(__HIPCC__)
+struct RecipTable { float v[kTile + 1]; };  // v[c] = 1.0f / (float)c, computed on the host
+
+template <typename E> struct Chunk;
+template <> struct Chunk<uint16_t> {  // bf16: 8 channels per 16 bytes
+    static constexpr int kN = 8;
+    __device__ static void unpack(const uint4& u, float* f) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f[2 * j] = __uint_as_float(w[j] << 16);
+            f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Chunk<uint32_t> {  // fp32: 4 channels per 16 bytes
+    static constexpr int kN = 4;
+    __device__ static void unpack(const uint4& u, float* f) {
+        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+    }
+};
+
 // Token index of slot l of tile i of a head, or -1 for a padded slot.  Tiles and slots are
 // both raster order with time slowest (App. A.5: temporal neighbours p_h*p_w slots apart).
 __device__ inline int slot_token(const HeadGeom& g, int i, int l, int T, int H, int W) {

@@ -25,8 +25,9 @@ VEDA_TOKEN_MAJOR, VEDA_CHANNEL_MAJOR = 0, 1
 EXPORTS = (
     "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
-    "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_select",
-    "veda_sparse_attn_fwd", "veda_status_string", "veda_last_error",
+    "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
+    "veda_tile_score_stats", "veda_tile_select", "veda_sparse_attn_fwd", "veda_status_string",
+    "veda_last_error",
 )
 
 
@@ -82,6 +83,11 @@ def load():
     L.veda_tile_score.argtypes = [vp, vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
                                   vp, vp, C.c_size_t, vp]
     L.veda_tile_score.restype = C.c_int
+    L.veda_tile_layout_stats.argtypes = [vp, vp, veda_strides, vp, vp, vp, vp, vp]
+    L.veda_tile_layout_stats.restype = C.c_int
+    L.veda_tile_score_stats.argtypes = [vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float, vp, vp,
+                                        C.c_size_t, vp]
+    L.veda_tile_score_stats.restype = C.c_int
     L.veda_tile_select.argtypes = [vp, vp, C.POINTER(i32), vp, vp, vp]
     L.veda_tile_select.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
@@ -211,6 +217,42 @@ def veda_tile_score(plan: Plan, q_tiled, k_tiled, valid_mask, phi_q: Mlp, phi_k:
     return scores, workspace
 
 
+def veda_tile_layout_stats(plan: Plan, x: torch.Tensor, x_tiled: Optional[torch.Tensor] = None,
+                           valid_mask: Optional[torch.Tensor] = None, valid_cnt: Optional[torch.Tensor] = None,
+                           stats: Optional[torch.Tensor] = None, want_mask: bool = True):
+    """Stage 1 (token-major) with the TripPool descriptors taken during the gather.
+    Returns (x_tiled, valid_mask, valid_cnt, stats fp32 [batch, total_tiles, 3*d])."""
+    dev = x.device
+    if x_tiled is None:
+        x_tiled = torch.empty((plan.batch, plan.total_tiles, 64 * plan.head_dim), dtype=x.dtype, device=dev)
+    if want_mask and valid_mask is None:
+        valid_mask = torch.empty(plan.total_tiles, dtype=torch.int64, device=dev)
+    if want_mask and valid_cnt is None:
+        valid_cnt = torch.empty(plan.total_tiles, dtype=torch.int32, device=dev)
+    if stats is None:
+        stats = torch.empty((plan.batch, plan.total_tiles, 3 * plan.head_dim), dtype=torch.float32, device=dev)
+    _check(load().veda_tile_layout_stats(plan.handle, _ptr(x), _strides(x), _ptr(x_tiled), _ptr(valid_mask),
+                                         _ptr(valid_cnt), _ptr(stats), _stream()), "veda_tile_layout_stats")
+    return x_tiled, valid_mask, valid_cnt, stats
+
+
+def veda_tile_score_stats(plan: Plan, stats_q, stats_k, phi_q: Mlp, phi_k: Mlp, scale: float,
+                          scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Stage 2 from descriptors.  Returns (scores fp32 [batch, score_elems], workspace holding the latents)."""
+    dev = stats_q.device
+    if scores is None:
+        scores = torch.empty((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
+    need = plan.batch * plan.total_tiles * 2 * phi_q.out_dim * 4
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    sq, sk = phi_q.struct(), phi_k.struct()
+    _check(load().veda_tile_score_stats(plan.handle, _ptr(stats_q), _ptr(stats_k), C.byref(sq), C.byref(sk),
+                                        C.c_float(scale), _ptr(scores), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()),
+           "veda_tile_score_stats")
+    return scores, workspace
+
+
 def veda_tile_select(plan: Plan, scores, k_per_head: Sequence[int], row_ptr: Optional[torch.Tensor] = None,
                      col_idx: Optional[torch.Tensor] = None):
     """Stage 3.  Returns (row_ptr i32 [batch*total_tiles+1], col_idx i32 [batch*nnz])."""
@@ -244,15 +286,25 @@ def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_
 
 
 def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,
-                   softmax_scale: float, buffers: Optional[dict] = None):
+                   softmax_scale: float, buffers: Optional[dict] = None, fused: bool = False):
     """The whole path in call order: layout x3 -> score -> select -> sparse attention.
+    fused=True takes the descriptors during the Q and K gathers (veda_tile_layout_stats +
+    veda_tile_score_stats); the results are bit-identical either way.
     `buffers` (optional dict) is filled on the first call and reused afterwards so that a
     steady-state step allocates nothing."""
     bufs = {} if buffers is None else buffers
-    qt, vm, vc = veda_tile_layout(plan, q, VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
-    kt, _, _ = veda_tile_layout(plan, k, VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
+    if fused:
+        qt, vm, vc, zq = veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"), bufs.get("zq"))
+        kt, _, _, zk = veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False)
+        bufs.update(zq=zq, zk=zk)
+    else:
+        qt, vm, vc = veda_tile_layout(plan, q, VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
+        kt, _, _ = veda_tile_layout(plan, k, VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
     vt, _, _ = veda_tile_layout(plan, v, VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
-    s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+    if fused:
+        s, ws = veda_tile_score_stats(plan, zq, zk, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+    else:
+        s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
     rp, ci = veda_tile_select(plan, s, k_per_head, bufs.get("rp"), bufs.get("ci"))
     out, _ = veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
     bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)

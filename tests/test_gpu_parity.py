@@ -190,6 +190,41 @@ def test_maximum_head_count():
         veda.Plan(1, 129, 64, wl.grid, np.tile(np.asarray([[4, 4, 4]], np.int32), (129, 1)), torch.bfloat16)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_descriptors_during_gather_are_bit_identical(dtype, d):
+    # veda_tile_layout_stats + veda_tile_score_stats against veda_tile_layout + veda_tile_score:
+    # same tiled bytes, masks, descriptors (also checked against the oracle) and scores
+    wl = wlm.custom_workload(f"fused_{dtype}_{d}", 5, d, dtype, (9, 10, 14), True, (25, 100), seed=51, batch=2,
+                             latent_dim=32)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+    pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+    scale = hz.score_scale_of(wl)
+    qt, vm, vc = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    s_ref, _ = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, scale)
+    qt2, vm2, vc2, zq = veda.veda_tile_layout_stats(plan, q)
+    kt2, _, _, zk = veda.veda_tile_layout_stats(plan, k, want_mask=False)
+    s2, _ = veda.veda_tile_score_stats(plan, zq, zk, pq, pk, scale)
+    torch.cuda.synchronize()
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(qt.view(view), qt2.view(view)) and torch.equal(kt.view(view), kt2.view(view))
+    assert torch.equal(vm, vm2) and torch.equal(vc, vc2)
+    assert torch.equal(s_ref.view(torch.int32), s2.view(torch.int32))
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            shape = tuple(int(x) for x in shapes[h])
+            nt, toff = plan.tiles[h], plan.tile_offset[h]
+            for x, z in ((q, zq), (k, zk)):
+                ref = vo.trippool(hz.to_f32_numpy(x[b, h]), wl.grid, shape)
+                got = z[b, toff:toff + nt].cpu().numpy()
+                assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (b, h)
+
+
 def test_select_on_constructed_ties_and_special_values():
     wl = wlm.custom_workload("ties", 2, 64, "f32", (4, 8, 40), False, (1, 4), seed=15, latent_dim=32)
     shapes = wlm.tile_shapes(wl)
