@@ -48,6 +48,8 @@ def lib():
         L.vo_masked_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32,
                                           f64, vp, i64, vp, vp, vp]
         L.vo_dense_attention.argtypes = [vp, vp, vp, i32, i64, f64, vp, i64, vp]
+        L.vo_tile_heatmap.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp, i64, vp]
+        L.vo_recall.argtypes = [vp, vp, i64, i32, vp]
         _lib = L
     return _lib
 
@@ -168,6 +170,32 @@ def dense_attention(q, k, v, scale: float, queries) -> np.ndarray:
     _ok(lib().vo_dense_attention(_p(q), _p(k), _p(v), q.shape[1], q.shape[0], float(scale),
                                  _p(queries), len(queries), _p(out)), "dense_attention")
     return out
+
+
+def tile_heatmap(q, k, grid, shape, scale: float, query_tiles=None) -> np.ndarray:
+    """Max-pooled full-attention probabilities per (query tile, key tile): [N_T, N_T] float64.
+    With query_tiles given, only those rows are computed; the others are NaN."""
+    q, k = _f32(q), _f32(k)
+    nt = num_tiles(grid, shape)
+    heat = np.full((nt, nt), np.nan, np.float64)
+    if query_tiles is None:
+        qt, n_qt = None, -1
+    else:
+        qt = np.ascontiguousarray(query_tiles, np.int32)
+        n_qt = len(qt)
+    _ok(lib().vo_tile_heatmap(_p(q), _p(k), q.shape[1], *map(int, grid), *map(int, shape), float(scale),
+                              _p(qt), n_qt, _p(heat)), "tile_heatmap")
+    return heat
+
+
+def recall(sel_sp: np.ndarray, sel_fu: np.ndarray) -> float:
+    """Tile recall of selection sel_sp against sel_fu, both [rows, k] lists of key tiles."""
+    a = np.ascontiguousarray(sel_sp, np.int32)
+    b = np.ascontiguousarray(sel_fu, np.int32)
+    assert a.shape == b.shape and a.ndim == 2
+    out = C.c_double(0.0)
+    _ok(lib().vo_recall(_p(a), _p(b), a.shape[0], a.shape[1], C.byref(out)), "recall")
+    return float(out.value)
 
 
 def estimate_and_select(q, k, grid, shape, phi_q, phi_k, head: int, ksel: int, scale=None):

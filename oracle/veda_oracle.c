@@ -384,3 +384,80 @@ int vo_dense_attention(const float* q, const float* k, const float* v, int d, in
     }
     return fail ? -3 : 0;
 }
+
+/* Target tile scores of full attention (Sec. 4.1 "Target: Full-Attention Score Construction"):
+ * A* = Softmax(Q K^T * scale) over all N tokens of the head, then max-pooling over each
+ * (query tile, key tile) region:  S_tgt[i][j] = max over tokens u of tile i, v of tile j of
+ * A*[u][v].  Padded slots hold no token and take no part.  The listed query tiles only
+ * (Sec. 4.3 "partial query processing": rows of other tiles are left untouched); n_qt < 0
+ * means all tiles.  heat is [N_T][N_T] row-major, double. */
+int vo_tile_heatmap(const float* q, const float* k, int d, int T, int H, int W, int pt, int ph, int pw,
+                    double scale, const int32_t* query_tiles, int64_t n_qt, double* heat) {
+    vo_geom g;
+    if (vo_make_geom(&g, T, H, W, pt, ph, pw)) return -1;
+    const int64_t N = (int64_t)T * H * W;
+    const int64_t NT = (int64_t)g.nt * g.nh * g.nw;
+    int32_t* tile_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    uint8_t* want = (uint8_t*)malloc((size_t)NT);
+    if (!tile_of || !want) { free(tile_of); free(want); return -3; }
+    vo_token_tile_map(T, H, W, pt, ph, pw, tile_of);
+    memset(want, n_qt < 0 ? 1 : 0, (size_t)NT);
+    for (int64_t r = 0; r < n_qt; ++r) {
+        if (query_tiles[r] < 0 || query_tiles[r] >= NT) { free(tile_of); free(want); return -2; }
+        want[query_tiles[r]] = 1;
+    }
+    for (int64_t i = 0; i < NT; ++i)
+        if (want[i]) for (int64_t j = 0; j < NT; ++j) heat[i * NT + j] = 0.0;
+    int fail = 0;
+    /* one query tile per iteration: its rows of heat are written by one thread only */
+#pragma omp parallel
+    {
+        double* a = (double*)malloc(sizeof(double) * (size_t)N);
+        if (!a) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t i = 0; i < NT; ++i) {
+            if (!a || !want[i]) continue;
+            for (int64_t u = 0; u < N; ++u) {
+                if (tile_of[u] != i) continue;
+                double mx = -INFINITY;
+                for (int64_t n = 0; n < N; ++n) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c) dot += (double)q[u * d + c] * (double)k[n * d + c];
+                    a[n] = dot * scale;
+                    if (a[n] > mx) mx = a[n];
+                }
+                double denom = 0.0;
+                for (int64_t n = 0; n < N; ++n) { a[n] = exp(a[n] - mx); denom += a[n]; }
+                for (int64_t n = 0; n < N; ++n) {
+                    const double p = a[n] / denom;
+                    double* cell = heat + i * NT + tile_of[n];
+                    if (p > *cell) *cell = p;
+                }
+            }
+        }
+        free(a);
+    }
+    free(tile_of);
+    free(want);
+    return fail ? -3 : 0;
+}
+
+/* Tile recall (Sec. 3.2 "Metric: tile recall w.r.t. full attention"):
+ * Recall@k = 1/rows * sum_i |S_sp_i  intersect  S_fu_i| / k, both selections given as
+ * [rows][k] lists of distinct key tiles in any order. */
+int vo_recall(const int32_t* sel_sp, const int32_t* sel_fu, int64_t rows, int k, double* recall) {
+    if (rows <= 0 || k <= 0) return -1;
+    double acc = 0.0;
+    for (int64_t i = 0; i < rows; ++i) {
+        int common = 0;
+        for (int a = 0; a < k; ++a)
+            for (int b = 0; b < k; ++b)
+                if (sel_sp[i * k + a] == sel_fu[i * k + b]) { ++common; break; }
+        acc += (double)common / (double)k;
+    }
+    *recall = acc / (double)rows;
+    return 0;
+}

@@ -87,3 +87,25 @@ def dense_attention64(q, k, v, scale):
     w = np.exp(logits)
     w /= w.sum(axis=1, keepdims=True)
     return w @ v, w
+
+
+def tile_heatmap64(q, k, grid, shape, scale):
+    """Sec. 4.1 target: full softmax in float64, then the maximum over every (query tile, key tile)
+    block of token pairs, by explicit enumeration of the tiles' members."""
+    q = np.asarray(q, np.float64)
+    k = np.asarray(k, np.float64)
+    logits = (q @ k.T) * scale
+    a = np.exp(logits - logits.max(axis=1, keepdims=True))
+    a /= a.sum(axis=1, keepdims=True)
+    mem = tile_members(grid, shape)
+    heat = np.zeros((len(mem), len(mem)))
+    for i, rows in enumerate(mem):
+        for j, cols in enumerate(mem):
+            heat[i, j] = a[np.ix_(rows, cols)].max()
+    return heat
+
+
+def recall64(sel_sp, sel_fu):
+    """Sec. 3.2 tile recall with Python sets."""
+    k = len(sel_sp[0])
+    return float(np.mean([len(set(map(int, a)) & set(map(int, b))) / k for a, b in zip(sel_sp, sel_fu)]))

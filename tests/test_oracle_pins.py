@@ -279,6 +279,62 @@ def test_planted_mistakes_are_caught_by_the_pins():
     assert not np.allclose(a, b)
 
 
+# ---------------------------------------------------------------- target heat map and recall
+@pytest.mark.parametrize("grid,shape", [((4, 8, 8), (4, 4, 4)), ((3, 9, 10), (1, 8, 8)), ((17, 3, 5), (16, 2, 2))])
+def test_tile_heatmap_against_brute_force(grid, shape):
+    n, d = int(np.prod(grid)), 8
+    q, k = 2.0 * _rand(n, d, 60), 2.0 * _rand(n, d, 61)
+    scale = 1.0 / np.sqrt(d)
+    heat = vo.tile_heatmap(q, k, grid, shape, scale)
+    ref = bf.tile_heatmap64(q, k, grid, shape, scale)
+    assert heat.shape == ref.shape and np.allclose(heat, ref, rtol=1e-10, atol=1e-15)
+    # a subset of query tiles gives the same rows and leaves the others alone
+    some = [0, heat.shape[0] - 1]
+    part = vo.tile_heatmap(q, k, grid, shape, scale, query_tiles=some)
+    assert np.array_equal(part[some], heat[some])
+    rest = np.setdiff1d(np.arange(heat.shape[0]), some)
+    assert np.isnan(part[rest]).all()
+
+
+def test_tile_heatmap_closed_forms():
+    grid, shape = (4, 8, 12), (4, 4, 4)        # 384 tokens, 6 full tiles
+    n, d = 384, 8
+    k = _rand(n, d, 62)
+    # zero queries: uniform attention, every block maximum is 1/N
+    heat = vo.tile_heatmap(np.zeros((n, d), np.float32), k, grid, shape, 0.3)
+    assert np.allclose(heat, 1.0 / n, rtol=1e-12)
+    # one key that every query prefers by a wide margin: its tile's column is ~1, the rest ~0
+    q = np.abs(_rand(n, d, 63)) + 0.5
+    kk = 0.01 * _rand(n, d, 64)
+    v_star = 200
+    kk[v_star] = 50.0
+    heat = vo.tile_heatmap(q, kk, grid, shape, 1.0)
+    j_star = vo.token_tile_map(grid, shape)[v_star]
+    assert np.all(heat[:, j_star] > 1.0 - 1e-9)
+    assert np.all(np.delete(heat, j_star, axis=1) < 1e-9)
+    # a block maximum is a probability; the maxima of a row of blocks cover the row's largest weight
+    q2, k2 = _rand(n, d, 65), _rand(n, d, 66)
+    heat = vo.tile_heatmap(q2, k2, grid, shape, 0.5)
+    assert np.all(heat > 0.0) and np.all(heat <= 1.0)
+    assert np.all(heat.sum(axis=1) >= 1.0 / 64)   # some query of the tile puts >= 1/N_T of its mass in one tile
+    # a ragged grid: padded slots take no part (same result as brute force above), and the
+    # scale matters
+    assert not np.allclose(heat, vo.tile_heatmap(q2, k2, grid, shape, 1.0))
+
+
+def test_recall_against_sets_and_hand_values():
+    rng = np.random.default_rng(67)
+    a = np.stack([rng.choice(40, 8, replace=False) for _ in range(25)]).astype(np.int32)
+    b = np.stack([rng.choice(40, 8, replace=False) for _ in range(25)]).astype(np.int32)
+    assert np.isclose(vo.recall(a, b), bf.recall64(a, b), rtol=0, atol=1e-15)
+    assert vo.recall(a, a[:, ::-1]) == 1.0
+    assert vo.recall(a, a + 40) == 0.0
+    assert vo.recall(np.array([[0, 1, 2, 3]], np.int32), np.array([[3, 9, 8, 0]], np.int32)) == 0.5
+    # top-k of the heat map against itself shifted by one tile: every row shares k-1 tiles
+    top = np.tile(np.arange(5, dtype=np.int32), (6, 1))
+    assert np.isclose(vo.recall(top, top + 1), 0.8)
+
+
 # ---------------------------------------------------------------- workloads feed
 def test_workload_sizes_match_the_size_table():
     w = wlm.WORKLOADS
