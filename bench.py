@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--dense", action="store_true", help="also time one dense (k = N_T) attention call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
+    ap.add_argument("--heatmap", action="store_true",
+                    help="also time the full-attention target tile scores (two dense Q K^T passes) and Recall@k")
     ap.add_argument("--unfused", action="store_true",
                     help="stage 2 re-reads the tiled Q and K for its descriptors (veda_tile_layout + veda_tile_score) "
                          "instead of taking them during the gathers")
@@ -226,6 +228,25 @@ def main():
                                "paper_context": "paper reports 10.5x self-attention / 5.1x end-to-end on NVIDIA Hopper "
                                                 "vs FlashAttention-3 with 128-token tiles (different hardware and baseline)"}
         del rp_d, ci_d
+
+    if args.heatmap:
+        # supervision side (not part of a step): two dense Q K^T passes over all tile pairs, then
+        # the recall of the estimator's selection against the selection from the target scores
+        heat = veda.veda_tile_heatmap(plan, bufs["qt"], bufs["kt"], bufs["vm"], softmax_scale)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        veda.veda_tile_heatmap(plan, bufs["qt"], bufs["kt"], bufs["vm"], softmax_scale, heat=heat)
+        e1.record()
+        torch.cuda.synchronize()
+        heat_ms = e0.elapsed_time(e1)
+        _, ci_t = veda.veda_tile_select(plan, heat, kph)
+        rec = veda.veda_tile_recall(plan, kph, bufs["ci"], ci_t)
+        torch.cuda.synchronize()
+        qk_flops = 2.0 * float((tiles * tiles).sum()) * wl.batch * 2 * 64 * 64 * d
+        result["heatmap_run"] = {"ms": heat_ms, "tflops_two_qk_passes_on_padded_tiles": qk_flops / (heat_ms * 1e-3) / 1e12,
+                                 "recall_at_k_random_init_estimator_mean": float(rec.mean().item())}
+        del heat, ci_t
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, shapes, kph, dense_flops, q, k, v, eq, ek, score_scale, softmax_scale)

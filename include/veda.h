@@ -158,6 +158,28 @@ veda_status veda_sparse_attn_fwd(const veda_plan*, const void* q_tiled, const vo
                                  const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
                                  void* out, veda_strides so, float* lse, void* stream);
 
+/* ---- supervision side: target tile scores of full attention and tile recall ------------- */
+/* veda_tile_heatmap (Sec. 4.1 Eq. 3; Sec. 4.3 "Efficient Ground-Truth Heatmap Generation"):
+ * heat     device fp32 [batch][score_elems], same per-head block layout as the scores of
+ *          stage 2: heat[i][j] = max over the real tokens u of query tile i and v of key tile j
+ *          of Softmax_v(q_u.k_v * softmax_scale), the softmax running over ALL real tokens of
+ *          the head (full attention).  Exact pooled values in two passes over the key tiles;
+ *          the attention map is never stored.
+ * query_tiles  optional device i32 [n_query_tiles] of global tile indices (tile_offset(h) + i,
+ *          each in [0, total_tiles), no index twice): only those rows of heat are written, for
+ *          every batch entry; NULL with n_query_tiles == 0 means all query tiles.
+ * q_tiled,k_tiled VEDA_TOKEN_MAJOR.  bf16: Q K^T on bf16 MFMA, fp32 accumulation and softmax. */
+veda_status veda_tile_heatmap(const veda_plan*, const void* q_tiled, const void* k_tiled,
+                              const uint64_t* valid_mask, float softmax_scale, const int32_t* query_tiles,
+                              int64_t n_query_tiles, float* heat, void* stream);
+/* veda_tile_recall (Sec. 3.2, Recall@k): col_idx_a, col_idx_b device CSR column lists as stage 3
+ * writes them for the same k_per_head (host i32 [heads]); each row a list of distinct tiles.
+ * recall   device fp32 [batch][heads]: mean over the head's query tiles of |A_i & B_i| / k.
+ * workspace device, 8-byte aligned, at least 8*batch*heads bytes. */
+veda_status veda_tile_recall(const veda_plan*, const int32_t* k_per_head, const int32_t* col_idx_a,
+                             const int32_t* col_idx_b, float* recall, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
 const char* veda_status_string(veda_status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */
 const char* veda_last_error(void);

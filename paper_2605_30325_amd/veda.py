@@ -26,8 +26,8 @@ EXPORTS = (
     "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
-    "veda_tile_score_stats", "veda_tile_select", "veda_sparse_attn_fwd", "veda_status_string",
-    "veda_last_error",
+    "veda_tile_score_stats", "veda_tile_select", "veda_sparse_attn_fwd", "veda_tile_heatmap",
+    "veda_tile_recall", "veda_status_string", "veda_last_error",
 )
 
 
@@ -92,6 +92,10 @@ def load():
     L.veda_tile_select.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
     L.veda_sparse_attn_fwd.restype = C.c_int
+    L.veda_tile_heatmap.argtypes = [vp, vp, vp, vp, C.c_float, vp, i64, vp, vp]
+    L.veda_tile_heatmap.restype = C.c_int
+    L.veda_tile_recall.argtypes = [vp, C.POINTER(i32), vp, vp, vp, vp, C.c_size_t, vp]
+    L.veda_tile_recall.restype = C.c_int
     L.veda_status_string.argtypes = [C.c_int]
     L.veda_status_string.restype = C.c_char_p
     L.veda_last_error.argtypes = []
@@ -283,6 +287,37 @@ def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_
                                        _ptr(valid_mask), _ptr(row_ptr), _ptr(col_idx), C.c_float(softmax_scale),
                                        _ptr(out), _strides(out), _ptr(lse), _stream()), "veda_sparse_attn_fwd")
     return out, lse
+
+
+def veda_tile_heatmap(plan: Plan, q_tiled, k_tiled, valid_mask, softmax_scale: float,
+                      query_tiles: Optional[torch.Tensor] = None, heat: Optional[torch.Tensor] = None):
+    """Target tile scores of full attention: heat fp32 [batch, score_elems] (rows of unlisted query
+    tiles are left as they were)."""
+    dev = q_tiled.device
+    if heat is None:
+        heat = torch.zeros((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
+    n_qt = 0 if query_tiles is None else int(query_tiles.numel())
+    _check(load().veda_tile_heatmap(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(valid_mask),
+                                    C.c_float(softmax_scale), _ptr(query_tiles), n_qt, _ptr(heat), _stream()),
+           "veda_tile_heatmap")
+    return heat
+
+
+def veda_tile_recall(plan: Plan, k_per_head: Sequence[int], col_idx_a, col_idx_b,
+                     recall: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Recall@k of selection a against selection b: fp32 [batch, heads]."""
+    k = np.ascontiguousarray(k_per_head, np.int32)
+    if k.size != plan.heads:
+        raise VedaError(VEDA_ERR_INVALID_ARG, "veda_tile_recall", "k_per_head must have one entry per head")
+    dev = col_idx_a.device
+    if recall is None:
+        recall = torch.empty((plan.batch, plan.heads), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(plan.batch * plan.heads, dtype=torch.int64, device=dev)
+    _check(load().veda_tile_recall(plan.handle, k.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(col_idx_a), _ptr(col_idx_b),
+                                   _ptr(recall), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream()), "veda_tile_recall")
+    return recall
 
 
 def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,

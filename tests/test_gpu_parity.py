@@ -347,3 +347,66 @@ def test_large_configs_sampled(name):
     # every real token of every head was written (the output buffer starts as NaN)
     for h in range(wl.heads):
         assert torch.isfinite(run.out[0, h].float()).all(), h
+
+
+# ---------------------------------------------------------------- supervision side
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_target_heatmap_and_recall(dtype, d):
+    # full-attention target tile scores (max-pooled softmax) and Recall@k against the oracle:
+    # ragged grid, odd tile counts, all three tile shapes, batch 2, then a subset of query tiles
+    wl = wlm.custom_workload(f"heat_{dtype}_{d}", 4, d, dtype, (9, 18, 18), True, (25, 100), seed=61, batch=2)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    scale = 1.0 / math.sqrt(d)
+    heat = veda.veda_tile_heatmap(plan, qt, kt, vm, scale)
+    torch.cuda.synchronize()
+    rtol = 2e-4 if dtype == "bf16" else 2e-5
+    refs = {}
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            shape = tuple(int(x) for x in shapes[h])
+            nt, soff = plan.tiles[h], plan.score_offset[h]
+            ref = vo.tile_heatmap(hz.to_f32_numpy(q[b, h]), hz.to_f32_numpy(k[b, h]), wl.grid, shape, scale)
+            got = heat[b, soff:soff + nt * nt].view(nt, nt).cpu().numpy().astype(np.float64)
+            rel = np.abs(got - ref) / ref
+            _say(f"[parity] {wl.name} b{b} h{h} {shape}: heat max rel err {rel.max():.2e}")
+            assert rel.max() <= rtol, (b, h, rel.max())
+            refs[(b, h)] = ref
+    # a subset of query tiles: listed rows equal the full run, the others are not touched
+    total = plan.total_tiles
+    some = np.asarray(sorted({0, 1, total // 2, total - 1, plan.tile_offset[1] + 3}), np.int32)
+    part = torch.full_like(heat, -7.0)
+    veda.veda_tile_heatmap(plan, qt, kt, vm, scale, torch.as_tensor(some).to(dev), part)
+    torch.cuda.synchronize()
+    for h in range(wl.heads):
+        nt, soff, toff = plan.tiles[h], plan.score_offset[h], plan.tile_offset[h]
+        a = part[:, soff:soff + nt * nt].view(wl.batch, nt, nt)
+        f = heat[:, soff:soff + nt * nt].view(wl.batch, nt, nt)
+        listed = np.asarray([g - toff for g in some if toff <= g < toff + nt], np.int64)
+        others = np.setdiff1d(np.arange(nt), listed)
+        assert torch.equal(a[:, listed], f[:, listed]) and bool((a[:, others] == -7.0).all())
+    # Recall@k of the estimator's selection against the selection from the target scores
+    kph = wlm.keep_budget(wl, None, shapes)
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    s_est, _ = veda.veda_tile_score(plan, qt, kt, vm, veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev),
+                                    veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev), hz.score_scale_of(wl))
+    _, ci_est = veda.veda_tile_select(plan, s_est, kph)
+    _, ci_tgt = veda.veda_tile_select(plan, heat, kph)
+    rec = veda.veda_tile_recall(plan, kph, ci_est, ci_tgt)
+    torch.cuda.synchronize()
+    a_np, b_np = ci_est.cpu().numpy(), ci_tgt.cpu().numpy()
+    nnz = int(sum(int(n) * int(kk) for n, kk in zip(plan.tiles, kph)))
+    off = 0
+    for h in range(wl.heads):
+        nt, kk = plan.tiles[h], int(kph[h])
+        for b in range(wl.batch):
+            lo = b * nnz + off
+            ref = vo.recall(a_np[lo:lo + nt * kk].reshape(nt, kk), b_np[lo:lo + nt * kk].reshape(nt, kk))
+            assert abs(float(rec[b, h]) - ref) <= 1e-6, (b, h, float(rec[b, h]), ref)
+        off += nt * kk
+    same = veda.veda_tile_recall(plan, kph, ci_tgt, ci_tgt)
+    assert bool((same == 1.0).all())
