@@ -198,6 +198,27 @@ def recall(sel_sp: np.ndarray, sel_fu: np.ndarray) -> float:
     return float(out.value)
 
 
+def tiling_search_errors(q, k, v, grid, candidates, keep, scale: float) -> np.ndarray:
+    """Alg. 1 (head-aware tiling search) for one head and one calibration sample: for every
+    candidate tile shape, the squared Frobenius distance between the full-attention output and
+    the tile-sparse output under the reference top-k mask of that tiling (Eq. 8's summand).
+    The reference mask is the per-row top-k (k = ceil(keep[0] * N_T / keep[1]), at least 1) of the
+    max-pooled full-attention map, rounded to fp32 before the selection (the precision the GPU
+    path selects in).  Returns float64 [len(candidates)]; argmin is the head's tiling."""
+    n = q.shape[0]
+    queries = np.arange(n)
+    o_full = dense_attention(q, k, v, scale, queries)
+    errs = np.empty(len(candidates), np.float64)
+    for c, shape in enumerate(candidates):
+        nt = num_tiles(grid, shape)
+        ksel = max(1, -(-keep[0] * nt // keep[1]))
+        heat = tile_heatmap(q, k, grid, shape, scale)
+        sel = select(heat.astype(np.float32), ksel)
+        o_sp = masked_attention(q, k, v, grid, shape, sel, scale, queries)
+        errs[c] = float(((o_full - o_sp) ** 2).sum())
+    return errs
+
+
 def estimate_and_select(q, k, grid, shape, phi_q, phi_k, head: int, ksel: int, scale=None):
     """Stages 2-3 for one head in the paper's order: TripPool -> phi -> score -> top-k.
     phi_* carry per-head arrays w1,b1,w2,b2 and out_dim.  Returns (z_q, z_k, qh, kh, s, idx)."""

@@ -335,6 +335,30 @@ def test_recall_against_sets_and_hand_values():
     assert np.isclose(vo.recall(top, top + 1), 0.8)
 
 
+def test_tiling_search_errors_against_brute_force_and_limits():
+    grid, n, d = (4, 8, 8), 256, 8
+    cands = [(4, 4, 4), (1, 8, 8), (2, 4, 8)]
+    q, k, v = 1.5 * _rand(n, d, 70), 1.5 * _rand(n, d, 71), _rand(n, d, 72)
+    scale = 1.0 / np.sqrt(d)
+    errs = vo.tiling_search_errors(q, k, v, grid, cands, (2, 4), scale)
+    o_full, _ = bf.dense_attention64(q, k, v, scale)
+    for c, shape in enumerate(cands):
+        heat = bf.tile_heatmap64(q, k, grid, shape, scale).astype(np.float32)
+        sel = bf.topk_rows(heat, 2)          # 4 tiles per tiling, keep 2/4
+        o_sp = bf.concat_tile_attention(q, k, v, grid, shape, sel, scale)
+        assert np.isclose(errs[c], ((o_full - o_sp) ** 2).sum(), rtol=1e-9)
+    assert np.all(errs > 0)
+    # keeping every tile reproduces full attention: the error vanishes for every tiling
+    full = vo.tiling_search_errors(q, k, v, grid, cands, (1, 1), scale)
+    assert np.all(full < 1e-20)
+    # a head whose attention is local in time only: tiles that are thin in time must lose
+    t_of = np.arange(n) // 64
+    qq = np.zeros((n, d), np.float32)
+    qq[np.arange(n), t_of] = 6.0
+    local = vo.tiling_search_errors(qq, qq.copy(), v, grid, [(1, 8, 8), (4, 4, 4)], (1, 4), 1.0)
+    assert local[0] < 1e-6 and local[1] > 1e-3 and int(np.argmin(local)) == 0
+
+
 # ---------------------------------------------------------------- workloads feed
 def test_workload_sizes_match_the_size_table():
     w = wlm.WORKLOADS
