@@ -180,6 +180,14 @@ veda_status veda_tile_recall(const veda_plan*, const int32_t* k_per_head, const 
                              const int32_t* col_idx_b, float* recall, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* veda_output_sqerr (Eq. 8; Alg. 1 "Compute Sparse Output and Error"): a, b device tensors in
+ * token order with strides sa, sb (plan dtype); err device fp64 [batch][heads] =
+ * sum over tokens and channels of (a - b)^2, accumulated in double in a fixed order.
+ * workspace device, 8-byte aligned, at least 8*64*batch*heads bytes.  The tiling search of
+ * Sec. 4.2 is this call around stages 1, heat map, 3 and 4 for every candidate tile shape. */
+veda_status veda_output_sqerr(const veda_plan*, const void* a, veda_strides sa, const void* b, veda_strides sb,
+                              double* err, void* workspace, size_t workspace_bytes, void* stream);
+
 const char* veda_status_string(veda_status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */
 const char* veda_last_error(void);

@@ -404,3 +404,81 @@ extern "C" veda_status veda_tile_recall(const veda_plan* pl, const int32_t* k_pe
                        recall, pl->prob.heads, n);
     return launch_status("veda_tile_recall");
 }
+
+// ---- squared Frobenius distance between two token-order tensors, per (batch, head) ----------
+// (Eq. 8 / Alg. 1: the error a candidate tiling is scored by).  Two deterministic stages: 64
+// workgroups per (batch, head) each reduce a contiguous share of the tokens in double precision
+// (fixed tree inside the workgroup), then one thread adds the 64 partial sums in order.
+namespace veda {
+
+constexpr int kErrParts = 64;
+
+template <typename E> __device__ __forceinline__ float err_elem(const char* p, int c);
+template <> __device__ __forceinline__ float err_elem<uint16_t>(const char* p, int c) {
+    return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(p)[c] << 16);
+}
+template <> __device__ __forceinline__ float err_elem<uint32_t>(const char* p, int c) {
+    return reinterpret_cast<const float*>(p)[c];
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void sqerr_partial_kernel(const char* __restrict__ a, int64_t ab, int64_t ah, int64_t an,
+                                                            const char* __restrict__ b, int64_t bb, int64_t bh, int64_t bn,
+                                                            double* __restrict__ partial, int64_t tokens, int d,
+                                                            int n_heads) {
+    __shared__ double red[256];
+    const int part = blockIdx.x, head = blockIdx.y, bt = blockIdx.z;
+    const int64_t per = (tokens + kErrParts - 1) / kErrParts;
+    const int64_t lo = part * per, hi = lo + per < tokens ? lo + per : tokens;
+    const char* pa = a + bt * ab + head * ah;
+    const char* pb = b + bt * bb + head * bh;
+    double acc = 0.0;
+    for (int64_t e = lo * d + threadIdx.x; e < hi * d; e += 256) {
+        const int64_t n = e / d;
+        const int c = (int)(e - n * d);
+        const float diff = err_elem<E>(pa + n * an, c) - err_elem<E>(pb + n * bn, c);
+        acc += (double)diff * (double)diff;
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[((int64_t)bt * n_heads + head) * kErrParts + part] = red[0];
+}
+
+__global__ void sqerr_finish_kernel(const double* __restrict__ partial, double* __restrict__ err, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    double acc = 0.0;
+    for (int p = 0; p < kErrParts; ++p) acc += partial[(int64_t)i * kErrParts + p];
+    err[i] = acc;
+}
+
+}  // namespace veda
+
+extern "C" veda_status veda_output_sqerr(const veda_plan* pl, const void* a, veda_strides sa, const void* b,
+                                         veda_strides sb, double* err, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+    using namespace veda;
+    if (!pl || !a || !b || !err) return VEDA_ERR_INVALID_ARG;
+    const int d = pl->prob.head_dim, es = pl->elem_size();
+    if (sa.n < d || sb.n < d || sa.b < 0 || sa.h < 0 || sb.b < 0 || sb.h < 0) return VEDA_ERR_INVALID_ARG;
+    const int n = pl->prob.batch * pl->prob.heads;
+    if (!workspace || workspace_bytes < sizeof(double) * (size_t)n * kErrParts) return VEDA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 7u) || (reinterpret_cast<uintptr_t>(err) & 7u)) return VEDA_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    double* partial = (double*)workspace;
+    dim3 grid(kErrParts, (unsigned)pl->prob.heads, (unsigned)pl->prob.batch);
+    if (es == 2)
+        hipLaunchKernelGGL(sqerr_partial_kernel<uint16_t>, grid, dim3(256), 0, s, (const char*)a, sa.b * es, sa.h * es,
+                           sa.n * es, (const char*)b, sb.b * es, sb.h * es, sb.n * es, partial, pl->tokens(), d,
+                           pl->prob.heads);
+    else
+        hipLaunchKernelGGL(sqerr_partial_kernel<uint32_t>, grid, dim3(256), 0, s, (const char*)a, sa.b * es, sa.h * es,
+                           sa.n * es, (const char*)b, sb.b * es, sb.h * es, sb.n * es, partial, pl->tokens(), d,
+                           pl->prob.heads);
+    hipLaunchKernelGGL(sqerr_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partial, err, n);
+    return launch_status("veda_output_sqerr");
+}

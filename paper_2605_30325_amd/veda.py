@@ -27,7 +27,7 @@ EXPORTS = (
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_select", "veda_sparse_attn_fwd", "veda_tile_heatmap",
-    "veda_tile_recall", "veda_status_string", "veda_last_error",
+    "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
 
 
@@ -96,6 +96,8 @@ def load():
     L.veda_tile_heatmap.restype = C.c_int
     L.veda_tile_recall.argtypes = [vp, C.POINTER(i32), vp, vp, vp, vp, C.c_size_t, vp]
     L.veda_tile_recall.restype = C.c_int
+    L.veda_output_sqerr.argtypes = [vp, vp, veda_strides, vp, veda_strides, vp, vp, C.c_size_t, vp]
+    L.veda_output_sqerr.restype = C.c_int
     L.veda_status_string.argtypes = [C.c_int]
     L.veda_status_string.restype = C.c_char_p
     L.veda_last_error.argtypes = []
@@ -318,6 +320,20 @@ def veda_tile_recall(plan: Plan, k_per_head: Sequence[int], col_idx_a, col_idx_b
                                    _ptr(recall), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream()), "veda_tile_recall")
     return recall
+
+
+def veda_output_sqerr(plan: Plan, a: torch.Tensor, b: torch.Tensor, err: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None):
+    """Squared Frobenius distance of two [batch, heads, N, d] tensors per (batch, head): fp64 [batch, heads]."""
+    dev = a.device
+    if err is None:
+        err = torch.empty((plan.batch, plan.heads), dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(plan.batch * plan.heads * 64, dtype=torch.float64, device=dev)
+    _check(load().veda_output_sqerr(plan.handle, _ptr(a), _strides(a), _ptr(b), _strides(b), _ptr(err),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "veda_output_sqerr")
+    return err
 
 
 def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,

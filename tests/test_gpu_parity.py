@@ -410,3 +410,39 @@ def test_target_heatmap_and_recall(dtype, d):
         off += nt * kk
     same = veda.veda_tile_recall(plan, kph, ci_tgt, ci_tgt)
     assert bool((same == 1.0).all())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiling_search_errors_and_choice(dtype):
+    # Alg. 1 on synthetic calibration tensors: error table against the oracle, same argmin where the
+    # oracle's margin is clear.  Head 0 attends within its own frame only, so the frame-shaped
+    # tiling must win it by a wide margin.
+    from paper_2605_30325_amd import search
+    grid, d, heads, samples = (8, 12, 16), 64, 3, 2
+    n = int(np.prod(grid))
+    cands = [(4, 4, 4), (1, 8, 8), (16, 2, 2)]
+    wl = wlm.custom_workload(f"search_{dtype}", heads, d, dtype, grid, False, (25, 100), seed=71, batch=samples)
+    dev = torch.device("cuda:0")
+    q, k, v = wlm.make_qkv(wl, dev)
+    frame = torch.arange(n, device=dev) // (grid[1] * grid[2])
+    onehot = torch.zeros((n, d), device=dev)
+    onehot[torch.arange(n, device=dev), frame] = 8.0
+    q[:, 0] = onehot.to(q.dtype)
+    k[:, 0] = onehot.to(k.dtype)
+    scale = 1.0 / math.sqrt(d)
+    best, table = search.tiling_search(q, k, v, grid, cands, (25, 100), scale)
+    torch.cuda.synchronize()
+    ref = np.zeros_like(table)
+    for h in range(heads):
+        for b in range(samples):
+            ref[h] += vo.tiling_search_errors(hz.to_f32_numpy(q[b, h]), hz.to_f32_numpy(k[b, h]),
+                                              hz.to_f32_numpy(v[b, h]), grid, cands, (25, 100), scale)
+    _say(f"[parity] tiling search {dtype}: gpu {table.tolist()} oracle {ref.tolist()} best {best.tolist()}")
+    # bf16 outputs carry 2^-9 relative rounding on both tensors: an absolute floor per table entry
+    floor = samples * n * d * (2.0 ** -8 * 0.5) ** 2 if dtype == "bf16" else 1e-6
+    assert np.all(np.abs(table - ref) <= 0.03 * ref + floor), (table, ref)
+    assert tuple(best[0]) == (1, 8, 8)
+    for h in range(heads):
+        order = np.sort(ref[h])
+        if order[1] - order[0] > 0.1 * order[1] + 2 * floor:
+            assert tuple(best[h]) == tuple(cands[int(np.argmin(ref[h]))]), (h, table[h], ref[h])
