@@ -446,3 +446,28 @@ def test_tiling_search_errors_and_choice(dtype):
         order = np.sort(ref[h])
         if order[1] - order[0] > 0.1 * order[1] + 2 * floor:
             assert tuple(best[h]) == tuple(cands[int(np.argmin(ref[h]))]), (h, table[h], ref[h])
+
+
+def test_target_heatmap_at_full_size_sampled_rows():
+    # the 32,760-token workload in the configuration bench.py --heatmap times: whole launch on the
+    # GPU, oracle on a seeded sample of query tiles (first and last included), all 624 columns
+    wl = wlm.WORKLOADS["wan1p3b_480p"]
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    scale = 1.0 / math.sqrt(wl.head_dim)
+    heat = veda.veda_tile_heatmap(plan, qt, kt, vm, scale)
+    torch.cuda.synchronize()
+    for h in (0, wl.heads - 1):
+        shape = tuple(int(x) for x in shapes[h])
+        nt, soff = plan.tiles[h], plan.score_offset[h]
+        rows = hz.sample_tiles(nt, 6, 100 + h)
+        ref = vo.tile_heatmap(hz.to_f32_numpy(q[0, h]), hz.to_f32_numpy(k[0, h]), wl.grid, shape, scale,
+                              query_tiles=rows)[rows]
+        got = heat[0, soff:soff + nt * nt].view(nt, nt)[torch.as_tensor(rows).to(dev)].cpu().numpy().astype(np.float64)
+        rel = np.abs(got - ref) / ref
+        _say(f"[parity] {wl.name} head {h}: target scores of {len(rows)} query tiles, max rel err {rel.max():.2e}")
+        assert rel.max() <= 2e-4
