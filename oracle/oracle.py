@@ -79,14 +79,15 @@ def token_tile_map(grid, shape) -> np.ndarray:
 
 
 def tile_layout(x: np.ndarray, grid, shape, channel_major: bool = False):
-    """x [N, d] of any fixed-size dtype -> (x_tiled, valid_mask u64 [N_T], valid_cnt i32 [N_T])."""
+    """x [N, d] of any fixed-size dtype -> (x_tiled, valid_mask u64 [N_T] (tiles of up to 64 tokens)
+    or [N_T, 2] (up to 128), valid_cnt i32 [N_T])."""
     x = np.ascontiguousarray(x)
     n, d = x.shape
     assert n == int(np.prod(grid))
     nt = num_tiles(grid, shape)
     b = int(np.prod(shape))
     out = np.empty((nt, d, b) if channel_major else (nt, b, d), x.dtype)
-    mask = np.empty(nt, np.uint64)
+    mask = np.empty(nt if b <= 64 else (nt, 2), np.uint64)
     cnt = np.empty(nt, np.int32)
     _ok(lib().vo_tile_layout(_p(x), x.dtype.itemsize, d, *map(int, grid), *map(int, shape),
                              int(channel_major), _p(out), _p(mask), _p(cnt)), "tile_layout")

@@ -70,8 +70,9 @@ int vo_token_tile_map(int T, int H, int W, int pt, int ph, int pw, int32_t* tile
  * x        [N][d]   elements of elem_size bytes, token order
  * x_tiled  token-major  [N_T][B][d]  (channel_major == 0)
  *          channel-major [N_T][d][B] (channel_major != 0)
- * Padded slots are zero bytes.  valid_mask[i] has bit l set iff slot l of tile i holds a
- * real token; valid_cnt[i] is its population count.  Byte moves only.
+ * Padded slots are zero bytes.  valid_mask holds ceil(B/64) words per tile: bit l%64 of word
+ * l/64 of tile i is set iff slot l holds a real token; valid_cnt[i] is the tile's population
+ * count.  B <= 128 (the paper's tile size, Sec. 4.2).  Byte moves only.
  */
 int vo_tile_layout(const void* x, int64_t elem_size, int d, int T, int H, int W,
                    int pt, int ph, int pw, int channel_major,
@@ -79,10 +80,11 @@ int vo_tile_layout(const void* x, int64_t elem_size, int d, int T, int H, int W,
     vo_geom g;
     if (vo_make_geom(&g, T, H, W, pt, ph, pw)) return -1;
     const int B = pt * ph * pw;
-    if (B > 64) return -2;
+    if (B > 128) return -2;
+    const int words = (B + 63) / 64;
     const int64_t n_tiles = (int64_t)g.nt * g.nh * g.nw;
     memset(x_tiled, 0, (size_t)(n_tiles * B * d * elem_size));
-    if (valid_mask) memset(valid_mask, 0, (size_t)n_tiles * sizeof(uint64_t));
+    if (valid_mask) memset(valid_mask, 0, (size_t)n_tiles * words * sizeof(uint64_t));
     if (valid_cnt) memset(valid_cnt, 0, (size_t)n_tiles * sizeof(int32_t));
     const char* src = (const char*)x;
     char* dst = (char*)x_tiled;
@@ -96,7 +98,7 @@ int vo_tile_layout(const void* x, int64_t elem_size, int d, int T, int H, int W,
                     const int64_t o = channel_major ? ((i * d + c) * B + l) : ((i * B + l) * d + c);
                     memcpy(dst + o * elem_size, src + (n * d + c) * elem_size, (size_t)elem_size);
                 }
-                if (valid_mask) valid_mask[i] |= (uint64_t)1 << l;
+                if (valid_mask) valid_mask[i * words + l / 64] |= (uint64_t)1 << (l % 64);
                 if (valid_cnt) valid_cnt[i] += 1;
             }
     return 0;

@@ -120,22 +120,24 @@ extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_t
     if (!aligned16(q_tiled) || !aligned16(k_tiled) || !aligned16(v_tiled) || !aligned16(out) ||
         (so.b * es) % 16 || (so.h * es) % 16 || (so.n * es) % 16)
         return VEDA_ERR_UNSUPPORTED;
+    // 128-token tiles: the kernel works on the 64-slot halves (inner plan), the CSR on whole tiles
+    const veda_plan* ip = pl->inner ? pl->inner : pl;
     AttnArgs a;
-    a.heads = pl->d_heads;
-    a.tile_head = pl->d_tile_head;
+    a.heads = ip->d_heads;
+    a.tile_head = ip->d_tile_head;
     a.q = (const char*)q_tiled; a.k = (const char*)k_tiled; a.v = (const char*)v_tiled;
     a.valid_mask = valid_mask; a.row_ptr = row_ptr; a.col_idx = col_idx;
     a.out = (char*)out; a.lse = lse;
-    a.total_tiles = pl->total_tiles;
-    a.rows = pl->total_tiles * pl->prob.batch;
+    a.total_tiles = ip->total_tiles;
+    a.rows = ip->total_tiles * pl->prob.batch;
     a.so_b = so.b * es; a.so_h = so.h * es; a.so_n = so.n * es;
     a.tokens = pl->tokens();
     a.n_heads = pl->prob.heads; a.T = pl->prob.T; a.H = pl->prob.H; a.W = pl->prob.W;
     a.scale_log2 = softmax_scale * kLog2e;
     hipStream_t s = (hipStream_t)stream;
     if (pl->prob.dtype == VEDA_BF16) {
-        a.xcd_cum = pl->d_xcd_cum_pair;
-        return launch_sparse_attn_bf16_pair(pl, a, s);
+        a.xcd_cum = ip->d_xcd_cum_pair;
+        return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, s);
     }
     a.xcd_cum = pl->d_xcd_cum;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_tiles), (unsigned)pl->prob.batch), block(256);

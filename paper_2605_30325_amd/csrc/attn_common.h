@@ -68,7 +68,8 @@ __device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base
                  : "memory", "m0");
 }
 
-// Launches the query-tile-pair bf16 kernel (attn_pair.hip); a.xcd_cum must be the pair table.
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, hipStream_t s);
+// Launches the query-tile-pair bf16 kernel (attn_pair.hip) on plan pl's geometry; a.xcd_cum must be
+// its pair table.  grouped: pl is the inner plan of 128-token tiles and the CSR counts whole tiles.
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s);
 
 }  // namespace veda

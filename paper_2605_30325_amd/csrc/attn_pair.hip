@@ -240,7 +240,10 @@ struct MergedStep {
     uint64_t vm;   // validity mask of key tile j
 };
 
-template <int D>
+// kGrouped: 128-token tiles.  The geometry in `a` is that of the 64-slot halves (tiles 2o, 2o+1
+// of whole tile o): the workgroup's pair IS one whole query tile, both halves keep the same list
+// (the CSR rows and entries count whole tiles), and every entry expands to its two halves.
+template <int D, bool kGrouped>
 __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs a) {
     constexpr int kRowB = D * 2;                 // bytes of one K row
     constexpr int kKBytes = kTile * kRowB;       // K tile
@@ -261,19 +264,20 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     const HeadGeom hg = a.heads[head];
     const int64_t b = blockIdx.y;
     const int qiA = 2 * pair;
-    const bool hasB = qiA + 1 < hg.n_tiles;
+    const bool hasB = kGrouped || qiA + 1 < hg.n_tiles;
     const int qi = (which == 0 || hasB) ? qiA + which : qiA;
-    const int64_t rowA = b * a.total_tiles + hg.tile_off + qiA;
+    const int64_t rowA = kGrouped ? b * (a.total_tiles / 2) + hg.tile_off / 2 + pair
+                                  : b * a.total_tiles + hg.tile_off + qiA;
     const int begA = a.row_ptr[rowA], endA = a.row_ptr[rowA + 1];
     const int nA = endA - begA;
-    const int nB = hasB ? a.row_ptr[rowA + 2] - endA : 0;
+    const int nB = kGrouped ? nA : (hasB ? a.row_ptr[rowA + 2] - endA : 0);
     // The kept lists and the validity masks are read-only for the whole launch and indexed
     // uniformly: reading them through the constant address space makes them scalar loads, so
     // no vector-memory counter waits of the compiler's own end up inside the main loop.
     typedef const __attribute__((address_space(4))) int32_t* const_i32_t;
     typedef const __attribute__((address_space(4))) uint64_t* const_u64_t;
     const const_i32_t colsA = (const_i32_t)(uintptr_t)(a.col_idx + begA);
-    const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + (hasB ? endA : begA));
+    const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + ((hasB && !kGrouped) ? endA : begA));
     const const_u64_t vmask = (const_u64_t)(uintptr_t)(a.valid_mask + hg.tile_off);
     const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
     const char* kt = a.k + head_tile0 * kKBytes;
@@ -343,22 +347,33 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     int ia = 0, ib = 0;
     int rawA = colsA[0], rawB = colsB[0];
     bool okA = nA > 0, okB = nB > 0;
+    int gh = 0;   // grouped walk: which half of the current entry comes next
 #define VEDA_NEXT_STEP(e)                                                            \
     do {                                                                             \
-        const int headA_ = okA ? rawA : kEnd, headB_ = okB ? rawB : kEnd;            \
-        const int j_ = headA_ < headB_ ? headA_ : headB_;                            \
-        const bool live_ = j_ != kEnd;                                               \
-        const int ta_ = (live_ && headA_ == j_) ? 1 : 0;                             \
-        const int tb_ = (live_ && headB_ == j_) ? 1 : 0;                             \
-        (e).j = live_ ? j_ : 0;                                                      \
-        (e).fl = ta_ | (tb_ << 1);                                                   \
-        (e).vm = vmask[(e).j];                                                       \
-        ia += ta_;                                                                   \
-        ib += tb_;                                                                   \
-        okA = ia < nA;                                                               \
-        okB = ib < nB;                                                               \
-        rawA = colsA[okA ? ia : 0];                                                  \
-        rawB = colsB[okB ? ib : 0];                                                  \
+        if (kGrouped) {                                                              \
+            (e).j = okA ? 2 * rawA + gh : 0;                                         \
+            (e).fl = okA ? 3 : 0;                                                    \
+            (e).vm = vmask[(e).j];                                                   \
+            ia += gh;                                                                \
+            gh ^= 1;                                                                 \
+            okA = ia < nA;                                                           \
+            rawA = colsA[okA ? ia : 0];                                              \
+        } else {                                                                     \
+            const int headA_ = okA ? rawA : kEnd, headB_ = okB ? rawB : kEnd;        \
+            const int j_ = headA_ < headB_ ? headA_ : headB_;                        \
+            const bool live_ = j_ != kEnd;                                           \
+            const int ta_ = (live_ && headA_ == j_) ? 1 : 0;                         \
+            const int tb_ = (live_ && headB_ == j_) ? 1 : 0;                         \
+            (e).j = live_ ? j_ : 0;                                                  \
+            (e).fl = ta_ | (tb_ << 1);                                               \
+            (e).vm = vmask[(e).j];                                                   \
+            ia += ta_;                                                               \
+            ib += tb_;                                                               \
+            okA = ia < nA;                                                           \
+            okB = ib < nB;                                                           \
+            rawA = colsA[okA ? ia : 0];                                              \
+            rawB = colsB[okB ? ib : 0];                                              \
+        }                                                                            \
     } while (0)
 
     // Step s (P = s & 1) computes on slot P while the tiles of step s+1 land in slot P^1.
@@ -391,12 +406,17 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     finish_pair<D>(st, a, hg, smem, head, qiA, hasB, b, tid, which, r, lq, hh);
 }
 
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, hipStream_t s) {
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s) {
     const int d = pl->prob.head_dim;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
     const size_t smem = (size_t)2 * 2 * kTile * d * 2;   // two slots of (K tile + V^T tile)
-    if (d == 128) hipLaunchKernelGGL(sparse_attn_bf16_pair_kernel<128>, grid, block, smem, s, a);
-    else hipLaunchKernelGGL(sparse_attn_bf16_pair_kernel<64>, grid, block, smem, s, a);
+    if (grouped) {
+        if (d == 128) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<128, true>), grid, block, smem, s, a);
+        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<64, true>), grid, block, smem, s, a);
+    } else {
+        if (d == 128) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<128, false>), grid, block, smem, s, a);
+        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<64, false>), grid, block, smem, s, a);
+    }
     return launch_status("sparse_attn_bf16_pair_kernel");
 }
 

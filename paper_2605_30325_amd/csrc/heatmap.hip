@@ -343,6 +343,7 @@ extern "C" veda_status veda_tile_heatmap(const veda_plan* pl, const void* q_tile
                                          void* stream) {
     using namespace veda;
     if (!pl || !q_tiled || !k_tiled || !valid_mask || !heat) return VEDA_ERR_INVALID_ARG;
+    if (pl->inner) return VEDA_ERR_UNSUPPORTED;   // 64-token tiles only
     if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return VEDA_ERR_INVALID_ARG;
     if (query_tiles ? (n_query_tiles < 1 || n_query_tiles > pl->total_tiles) : n_query_tiles != 0)
         return VEDA_ERR_INVALID_ARG;

@@ -91,6 +91,12 @@ __global__ __launch_bounds__(256) void layout_channel_major_kernel(
     }
 }
 
+// 128-token tiles: number of real tokens of a whole tile from the masks of its two halves.
+__global__ void valid_cnt_pairs_kernel(const uint64_t* __restrict__ mask, int32_t* __restrict__ cnt, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) cnt[i] = __popcll(mask[2 * i]) + __popcll(mask[2 * i + 1]);
+}
+
 // Token-major tiling with the TripPool descriptors (Eq. 4: Avg | Max | Min over the tile's real
 // tokens, per channel) taken on the way, so the tiled tensor is not read back for them.
 // One thread owns 16 bytes of the channel axis of one tile and walks its 64 slots in order:
@@ -180,24 +186,31 @@ extern "C" veda_status veda_tile_layout(const veda_plan* pl, const void* x, veda
     if (!aligned16(x) || !aligned16(x_tiled) || (sx.b * es) % 16 || (sx.h * es) % 16 || (sx.n * es) % 16)
         return VEDA_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
-    dim3 grid((unsigned)pl->total_tiles, (unsigned)pl->prob.batch);
+    // 128-token tiles are laid out as their two 64-slot halves (tiles 2o, 2o+1 of the inner plan)
+    const veda_plan* ip = pl->inner ? pl->inner : pl;
+    if (pl->inner && valid_cnt && !valid_mask) return VEDA_ERR_INVALID_ARG;   // counts come from the masks
+    int32_t* cnt_arg = pl->inner ? nullptr : valid_cnt;
+    dim3 grid((unsigned)ip->total_tiles, (unsigned)pl->prob.batch);
     const int64_t sb = sx.b * es, sh = sx.h * es, sn = sx.n * es;
     const int T = pl->prob.T, H = pl->prob.H, W = pl->prob.W;
     if (order == VEDA_TOKEN_MAJOR) {
-        hipLaunchKernelGGL(layout_token_major_kernel, grid, dim3(256), 0, st, pl->d_heads, pl->d_tile_head,
-                           (const char*)x, sb, sh, sn, (char*)x_tiled, pl->total_tiles, d * es, T, H, W,
-                           valid_mask, valid_cnt);
+        hipLaunchKernelGGL(layout_token_major_kernel, grid, dim3(256), 0, st, ip->d_heads, ip->d_tile_head,
+                           (const char*)x, sb, sh, sn, (char*)x_tiled, ip->total_tiles, d * es, T, H, W,
+                           valid_mask, cnt_arg);
     } else {
 #define VEDA_LAUNCH_CM(E, D)                                                                           \
-    hipLaunchKernelGGL((layout_channel_major_kernel<E, D>), grid, dim3(256), 0, st, pl->d_heads,        \
-                       pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, pl->total_tiles, T, \
-                       H, W, valid_mask, valid_cnt)
+    hipLaunchKernelGGL((layout_channel_major_kernel<E, D>), grid, dim3(256), 0, st, ip->d_heads,        \
+                       ip->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, ip->total_tiles, T, \
+                       H, W, valid_mask, cnt_arg)
         if (es == 2 && d == 128) VEDA_LAUNCH_CM(uint16_t, 128);
         else if (es == 2 && d == 64) VEDA_LAUNCH_CM(uint16_t, 64);
         else if (es == 4 && d == 128) VEDA_LAUNCH_CM(uint32_t, 128);
         else VEDA_LAUNCH_CM(uint32_t, 64);
 #undef VEDA_LAUNCH_CM
     }
+    if (pl->inner && valid_cnt)
+        hipLaunchKernelGGL(valid_cnt_pairs_kernel, dim3((unsigned)((pl->total_tiles + 255) / 256)), dim3(256), 0, st,
+                           valid_mask, valid_cnt, pl->total_tiles);
     return launch_status("veda_tile_layout");
 }
 
@@ -206,6 +219,7 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
                                               void* stream) {
     using namespace veda;
     if (!pl || !x || !x_tiled || !stats) return VEDA_ERR_INVALID_ARG;
+    if (pl->inner) return VEDA_ERR_UNSUPPORTED;   // 64-token tiles only
     const int es = pl->elem_size();
     const int d = pl->prob.head_dim;
     if (sx.n < d || sx.b < 0 || sx.h < 0) return VEDA_ERR_INVALID_ARG;
@@ -217,7 +231,7 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
     const int T = pl->prob.T, H = pl->prob.H, W = pl->prob.W;
     RecipTable recip;
     recip.v[0] = 0.0f;
-    for (int c = 1; c <= kTile; ++c) recip.v[c] = 1.0f / (float)c;
+    for (int c = 1; c <= 2 * kTile; ++c) recip.v[c] = 1.0f / (float)c;
 #define VEDA_LAUNCH_LS(E, D)                                                                              \
     do {                                                                                                  \
         constexpr int tiles = 256 / (D / Chunk<E>::kN);                                                   \

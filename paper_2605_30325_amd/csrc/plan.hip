@@ -34,34 +34,31 @@ const char* veda_status_string(veda_status s) {
 
 const char* veda_last_error(void) { return veda::g_last_error.c_str(); }
 
-veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
-    if (!p || !out || !p->tile_shape) return VEDA_ERR_INVALID_ARG;
-    if (p->batch < 1 || p->heads < 1 || p->T < 1 || p->H < 1 || p->W < 1) return VEDA_ERR_INVALID_ARG;
-    if (p->dtype != VEDA_F32 && p->dtype != VEDA_BF16) return VEDA_ERR_INVALID_ARG;
-    if (p->tile_tokens != veda::kTile) return VEDA_ERR_UNSUPPORTED;
-    if (p->head_dim != 64 && p->head_dim != 128) return VEDA_ERR_UNSUPPORTED;
-    if (p->heads > veda::kMaxHeads) return VEDA_ERR_UNSUPPORTED;
-    if ((int64_t)p->T * p->H * p->W > (int64_t)1 << 30) return VEDA_ERR_UNSUPPORTED;
-    for (int h = 0; h < p->heads; ++h) {
-        const int32_t* s = p->tile_shape + 3 * h;
-        if (s[0] < 1 || s[1] < 1 || s[2] < 1) return VEDA_ERR_INVALID_ARG;
-        if ((int64_t)s[0] * s[1] * s[2] != p->tile_tokens) return VEDA_ERR_INVALID_ARG;
-    }
-
+// Builds one plan object.  grp = 1: tiles of prob.tile_tokens tokens with the given extents.
+// grp = 2: the 64-slot halves of 128-token tiles whose extents are `shapes` (halves 2o, 2o+1).
+static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int grp, veda_plan** out) {
     veda_plan* pl = new (std::nothrow) veda_plan();
     if (!pl) return VEDA_ERR_INVALID_ARG;
     pl->prob = *p;
-    pl->shapes.assign(p->tile_shape, p->tile_shape + 3 * p->heads);
+    pl->shapes.assign(shapes, shapes + 3 * p->heads);
     pl->prob.tile_shape = pl->shapes.data();
     pl->heads.resize(p->heads);
     int64_t toff = 0, soff = 0, boff = 0;
     for (int h = 0; h < p->heads; ++h) {
         HeadGeom& g = pl->heads[h];
-        g.pt = pl->shapes[3 * h]; g.ph = pl->shapes[3 * h + 1]; g.pw = pl->shapes[3 * h + 2];
-        g.nt = (p->T + g.pt - 1) / g.pt;
-        g.nh = (p->H + g.ph - 1) / g.ph;
-        g.nw = (p->W + g.pw - 1) / g.pw;
-        const int64_t n = (int64_t)g.nt * g.nh * g.nw;
+        g.ot = pl->shapes[3 * h]; g.oh = pl->shapes[3 * h + 1]; g.ow = pl->shapes[3 * h + 2];
+        g.pt = g.ot; g.ph = g.oh; g.pw = g.ow;
+        g.ht = g.hh = g.hw = 0;
+        g.grp = grp;
+        if (grp == 2) {   // cut across the slowest axis of extent > 1 (a product of 128: it is even)
+            if (g.ot > 1) { g.pt = g.ot / 2; g.ht = g.pt; }
+            else if (g.oh > 1) { g.ph = g.oh / 2; g.hh = g.ph; }
+            else { g.pw = g.ow / 2; g.hw = g.pw; }
+        }
+        g.nt = (p->T + g.ot - 1) / g.ot;
+        g.nh = (p->H + g.oh - 1) / g.oh;
+        g.nw = (p->W + g.ow - 1) / g.ow;
+        const int64_t n = (int64_t)grp * g.nt * g.nh * g.nw;
         g.n_tiles = (int32_t)n;
         g.tile_off = (int32_t)toff;
         g.score_off = soff;
@@ -132,8 +129,37 @@ veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
     return VEDA_OK;
 }
 
+veda_status veda_plan_create(const veda_problem* p, veda_plan** out) {
+    if (!p || !out || !p->tile_shape) return VEDA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->heads < 1 || p->T < 1 || p->H < 1 || p->W < 1) return VEDA_ERR_INVALID_ARG;
+    if (p->dtype != VEDA_F32 && p->dtype != VEDA_BF16) return VEDA_ERR_INVALID_ARG;
+    if (p->tile_tokens != veda::kTile && p->tile_tokens != 2 * veda::kTile) return VEDA_ERR_UNSUPPORTED;
+    if (p->tile_tokens == 2 * veda::kTile && p->dtype != VEDA_BF16) return VEDA_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128) return VEDA_ERR_UNSUPPORTED;
+    if (p->heads > veda::kMaxHeads) return VEDA_ERR_UNSUPPORTED;
+    if ((int64_t)p->T * p->H * p->W > (int64_t)1 << 30) return VEDA_ERR_UNSUPPORTED;
+    for (int h = 0; h < p->heads; ++h) {
+        const int32_t* s = p->tile_shape + 3 * h;
+        if (s[0] < 1 || s[1] < 1 || s[2] < 1) return VEDA_ERR_INVALID_ARG;
+        if ((int64_t)s[0] * s[1] * s[2] != p->tile_tokens) return VEDA_ERR_INVALID_ARG;
+    }
+    veda_plan* pl = nullptr;
+    veda_status st = build_plan(p, p->tile_shape, 1, &pl);
+    if (st != VEDA_OK) return st;
+    if (p->tile_tokens == 2 * veda::kTile) {
+        st = build_plan(p, p->tile_shape, 2, &pl->inner);
+        if (st != VEDA_OK) {
+            veda_plan_destroy(pl);
+            return st;
+        }
+    }
+    *out = pl;
+    return VEDA_OK;
+}
+
 void veda_plan_destroy(veda_plan* pl) {
     if (!pl) return;
+    veda_plan_destroy(pl->inner);
     if (pl->d_heads) (void)hipFree(pl->d_heads);
     if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
     if (pl->d_xcd_cum) (void)hipFree(pl->d_xcd_cum);

@@ -14,9 +14,11 @@
 
 namespace veda {
 
-// One thread owns kN channels of one tile and walks its 64 slots in order.
+// One thread owns kN channels of one tile and walks its slots in order (kWords = 1: 64-token
+// tiles; kWords = 2: 128-token tiles, stored as two consecutive 64-slot halves with one mask
+// word each, so slot order is unchanged).
 // grid = (ceil(rows / tiles_per_block), 2 tensors); rows = batch * total_tiles.
-template <typename E, int D>
+template <typename E, int D, int kWords>
 __global__ __launch_bounds__(256) void trippool_kernel(const char* __restrict__ q_tiled,
                                                        const char* __restrict__ k_tiled,
                                                        const uint64_t* __restrict__ valid_mask,
@@ -25,18 +27,27 @@ __global__ __launch_bounds__(256) void trippool_kernel(const char* __restrict__ 
     constexpr int kN = Chunk<E>::kN;
     constexpr int kTpt = D / kN;                 // threads per tile
     constexpr int kRowBytes = D * (int)sizeof(E);
+    constexpr int kSlots = kWords * kTile;
     const int64_t row = (int64_t)blockIdx.x * (256 / kTpt) + threadIdx.x / kTpt;
     if (row >= rows) return;
     const int chunk = threadIdx.x % kTpt;
-    const char* src = (blockIdx.y == 0 ? q_tiled : k_tiled) + row * (int64_t)kTile * kRowBytes + chunk * 16;
+    const char* src = (blockIdx.y == 0 ? q_tiled : k_tiled) + row * (int64_t)kSlots * kRowBytes + chunk * 16;
     float* z = (blockIdx.y == 0 ? zq : zk) + row * (3 * D) + chunk * kN;
-    const uint64_t mask = valid_mask[row % total_tiles];
+    uint64_t mask[kWords];
+    bool full = true;
+    int count = 0;
+#pragma unroll
+    for (int w = 0; w < kWords; ++w) {
+        mask[w] = valid_mask[(row % total_tiles) * kWords + w];
+        full = full && mask[w] == ~0ull;
+        count += __popcll(mask[w]);
+    }
     float sum[kN], mx[kN], mn[kN];
 #pragma unroll
     for (int j = 0; j < kN; ++j) { sum[j] = 0.0f; mx[j] = -INFINITY; mn[j] = INFINITY; }
-    if (mask == ~0ull) {
+    if (full) {
 #pragma unroll 8
-        for (int l = 0; l < kTile; ++l) {
+        for (int l = 0; l < kSlots; ++l) {
             float f[kN];
             Chunk<E>::unpack(*reinterpret_cast<const uint4*>(src + l * kRowBytes), f);
 #pragma unroll
@@ -47,19 +58,22 @@ __global__ __launch_bounds__(256) void trippool_kernel(const char* __restrict__ 
             }
         }
     } else {
-        for (int l = 0; l < kTile; ++l) {
-            if (!((mask >> l) & 1ull)) continue;
-            float f[kN];
-            Chunk<E>::unpack(*reinterpret_cast<const uint4*>(src + l * kRowBytes), f);
 #pragma unroll
-            for (int j = 0; j < kN; ++j) {
-                sum[j] = sum[j] + f[j];
-                mx[j] = f[j] > mx[j] ? f[j] : mx[j];
-                mn[j] = f[j] < mn[j] ? f[j] : mn[j];
+        for (int w = 0; w < kWords; ++w) {
+            for (int l = 0; l < kTile; ++l) {
+                if (!((mask[w] >> l) & 1ull)) continue;
+                float f[kN];
+                Chunk<E>::unpack(*reinterpret_cast<const uint4*>(src + (w * kTile + l) * kRowBytes), f);
+#pragma unroll
+                for (int j = 0; j < kN; ++j) {
+                    sum[j] = sum[j] + f[j];
+                    mx[j] = f[j] > mx[j] ? f[j] : mx[j];
+                    mn[j] = f[j] < mn[j] ? f[j] : mn[j];
+                }
             }
         }
     }
-    const float inv = recip.v[__popcll(mask)];
+    const float inv = recip.v[count];
 #pragma unroll
     for (int j = 0; j < kN; ++j) {
         z[j] = sum[j] * inv;
@@ -344,7 +358,7 @@ static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q,
 
 static void fill_recip(RecipTable& recip) {
     recip.v[0] = 0.0f;
-    for (int c = 1; c <= kTile; ++c) recip.v[c] = 1.0f / (float)c;
+    for (int c = 1; c <= 2 * kTile; ++c) recip.v[c] = 1.0f / (float)c;
 }
 
 }  // namespace veda
@@ -378,8 +392,12 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     do {                                                                                                   \
         constexpr int tpb = 256 / (D / Chunk<E>::kN);                                                      \
         dim3 grid((unsigned)((rows + tpb - 1) / tpb), 2);                                                  \
-        hipLaunchKernelGGL((trippool_kernel<E, D>), grid, dim3(256), 0, s, (const char*)q_tiled,           \
-                           (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);                  \
+        if (pl->inner)                                                                                     \
+            hipLaunchKernelGGL((trippool_kernel<E, D, 2>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
+                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
+        else                                                                                               \
+            hipLaunchKernelGGL((trippool_kernel<E, D, 1>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
+                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
     } while (0)
     if (bf16 && d == 128) VEDA_LAUNCH_TP(uint16_t, 128);
     else if (bf16) VEDA_LAUNCH_TP(uint16_t, 64);

@@ -17,18 +17,28 @@ constexpr int kMaxHeads = 128;   // per-call tables passed by value are sized fo
 constexpr int kXcd = 8;          // accelerator dies (each with its own L2); workgroup i runs on die i % 8
 
 // Per-head geometry, one entry per head, in device memory (plan->d_heads).
+//
+// 128-token tiles are handled as two 64-slot halves: a tile of extents (ot,oh,ow) is cut across
+// its slowest axis of extent > 1, so that slots 0-63 are one half and slots 64-127 the other, and
+// the two halves are tiles 2o and 2o+1 of an "inner" geometry (grp = 2).  There pt,ph,pw are
+// the extents of a half, (ht,hh,hw) the token offset of the second half inside the whole tile,
+// and nt,nh,nw still count whole tiles.  For 64-token tiles grp = 1, (ot,oh,ow) = (pt,ph,pw)
+// and the offsets are zero.
 struct HeadGeom {
-    int32_t pt, ph, pw;      // tile extents
-    int32_t nt, nh, nw;      // tile grid (ceil)
-    int32_t n_tiles;         // nt*nh*nw
+    int32_t pt, ph, pw;      // extents of one 64-slot tile (or half tile)
+    int32_t nt, nh, nw;      // grid of whole tiles (ceil)
+    int32_t n_tiles;         // number of 64-slot tiles: grp*nt*nh*nw
     int32_t tile_off;        // first global tile index of this head
     int64_t score_off;       // first score element of this head (per batch)
     int32_t score_blk_off;   // first 128x128 score block of this head
     int32_t score_blk_dim;   // ceil(n_tiles / 128)
+    int32_t ot, oh, ow;      // extents of a whole tile
+    int32_t ht, hh, hw;      // token offset of the second half inside a whole tile
+    int32_t grp;             // 64-slot tiles per whole tile: 1 or 2
 };
 
 #if defined(__HIPCC__)
-struct RecipTable { float v[kTile + 1]; };  // v[c] = 1.0f / (float)c, computed on the host
+struct RecipTable { float v[2 * kTile + 1]; };  // v[c] = 1.0f / (float)c, computed on the host
 
 template <typename E> struct Chunk;
 template <> struct Chunk<uint16_t> {  // bf16: 8 channels per 16 bytes
@@ -53,9 +63,10 @@ template <> struct Chunk<uint32_t> {  // fp32: 4 channels per 16 bytes
 // Token index of slot l of tile i of a head, or -1 for a padded slot.  Tiles and slots are
 // both raster order with time slowest (App. A.5: temporal neighbours p_h*p_w slots apart).
 __device__ inline int slot_token(const HeadGeom& g, int i, int l, int T, int H, int W) {
-    const int tw = i % g.nw, th = (i / g.nw) % g.nh, tt = i / (g.nw * g.nh);
+    const int o = g.grp == 2 ? i >> 1 : i, half = g.grp == 2 ? (i & 1) : 0;
+    const int tw = o % g.nw, th = (o / g.nw) % g.nh, tt = o / (g.nw * g.nh);
     const int lw = l % g.pw, lh = (l / g.pw) % g.ph, lt = l / (g.pw * g.ph);
-    const int t = tt * g.pt + lt, h = th * g.ph + lh, w = tw * g.pw + lw;
+    const int t = tt * g.ot + half * g.ht + lt, h = th * g.oh + half * g.hh + lh, w = tw * g.ow + half * g.hw + lw;
     return (t < T && h < H && w < W) ? (t * H + h) * W + w : -1;
 }
 #endif
@@ -70,6 +81,9 @@ struct veda_plan {
     int64_t score_elems = 0;
     int64_t score_blocks = 0;
     int device = -1;
+    // 128-token tiles: this plan describes the whole tiles (stages 2 and 3 work on them); `inner`
+    // describes their 64-slot halves, in the order 2o, 2o+1 (stages 1 and 4 work on those).
+    veda_plan* inner = nullptr;
     veda::HeadGeom* d_heads = nullptr;  // device [heads]
     uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
     // Blocks of 64 consecutive tiles that never straddle two heads (the projection kernel's work

@@ -169,6 +169,8 @@ class Plan:
         _check(L.veda_plan_create(C.byref(prob), C.byref(h)), "veda_plan_create")
         self.handle = h
         self.batch, self.heads, self.head_dim, self.grid, self.dtype = batch, heads, head_dim, tuple(grid), dtype
+        self.tile_tokens = int(tile_tokens)        # 64, or 128 (two 64-slot halves per tile)
+        self.mask_words = self.tile_tokens // 64   # u64 words of valid_mask per tile
         self.tokens = int(grid[0]) * int(grid[1]) * int(grid[2])
         self.tiles = [int(L.veda_plan_tiles(h, i)) for i in range(heads)]
         self.tile_offset = [int(L.veda_plan_tile_offset(h, i)) for i in range(heads)]
@@ -194,12 +196,14 @@ class Plan:
 def veda_tile_layout(plan: Plan, x: torch.Tensor, order: int = VEDA_TOKEN_MAJOR,
                      x_tiled: Optional[torch.Tensor] = None, valid_mask: Optional[torch.Tensor] = None,
                      valid_cnt: Optional[torch.Tensor] = None, want_mask: bool = True):
-    """Stage 1.  Returns (x_tiled [batch, total_tiles, 64*d], valid_mask i64-as-u64, valid_cnt i32)."""
+    """Stage 1.  Returns (x_tiled [batch, total_tiles, tile_tokens*d], valid_mask i64-as-u64
+    [total_tiles * tile_tokens/64], valid_cnt i32 [total_tiles])."""
     dev = x.device
     if x_tiled is None:
-        x_tiled = torch.empty((plan.batch, plan.total_tiles, 64 * plan.head_dim), dtype=x.dtype, device=dev)
+        x_tiled = torch.empty((plan.batch, plan.total_tiles, plan.tile_tokens * plan.head_dim), dtype=x.dtype,
+                              device=dev)
     if want_mask and valid_mask is None:
-        valid_mask = torch.empty(plan.total_tiles, dtype=torch.int64, device=dev)
+        valid_mask = torch.empty(plan.total_tiles * plan.mask_words, dtype=torch.int64, device=dev)
     if want_mask and valid_cnt is None:
         valid_cnt = torch.empty(plan.total_tiles, dtype=torch.int32, device=dev)
     _check(load().veda_tile_layout(plan.handle, _ptr(x), _strides(x), order, _ptr(x_tiled), _ptr(valid_mask),

@@ -471,3 +471,67 @@ def test_target_heatmap_at_full_size_sampled_rows():
         rel = np.abs(got - ref) / ref
         _say(f"[parity] {wl.name} head {h}: target scores of {len(rows)} query tiles, max rel err {rel.max():.2e}")
         assert rel.max() <= 2e-4
+
+
+# ---------------------------------------------------------------- 128-token tiles
+@pytest.mark.parametrize("d", [128, 64])
+def test_128_token_tiles_whole_path(d):
+    # the paper's tile size: every stage against the oracle with 128-token tile shapes whose halves
+    # are cut across t, h or w; ragged on every axis; batch 2
+    shapes = np.asarray([(8, 4, 4), (2, 8, 8), (32, 2, 2), (1, 8, 16), (1, 1, 128)], np.int32)
+    wl = wlm.custom_workload(f"b128_{d}", len(shapes), d, "bf16", (9, 18, 18), True, (25, 100), seed=81, batch=2,
+                             latent_dim=32)
+    dev = torch.device("cuda:0")
+    q, k, v = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, d, wl.grid, shapes, wl.torch_dtype, tile_tokens=128)
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+    pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+    sscale = hz.score_scale_of(wl)
+    scale = 1.0 / math.sqrt(d)
+    qt, vm, vc = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, want_mask=False)
+    s, _ = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, sscale)
+    kph = np.asarray([max(1, -(-n // 4)) for n in plan.tiles], np.int32)
+    rp, ci = veda.veda_tile_select(plan, s, kph)
+    out = torch.full((wl.batch, wl.heads, wl.tokens, d), float("nan"), dtype=wl.torch_dtype, device=dev)
+    out, lse = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, scale, out=out, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    with pytest.raises(veda.VedaError):
+        veda.veda_tile_heatmap(plan, qt, kt, vm, scale)      # 64-token tiles only
+    rp_np, ci_np = rp.cpu().numpy(), ci.cpu().numpy()
+    vm_np = vm.cpu().numpy().view(np.uint64).reshape(-1, 2)
+    queries = np.arange(wl.tokens)
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            shape = tuple(int(x) for x in shapes[h])
+            nt, toff, soff, ksel = plan.tiles[h], plan.tile_offset[h], plan.score_offset[h], int(kph[h])
+            assert nt == vo.num_tiles(wl.grid, shape)
+            qh, kh, vh = q[b, h], k[b, h], v[b, h]
+            ref_q, mask, cnt = vo.tile_layout(hz.raw_numpy(qh), wl.grid, shape)
+            assert np.array_equal(hz.raw_numpy(qt[b, toff:toff + nt]).reshape(ref_q.shape), ref_q)
+            assert np.array_equal(vm_np[toff:toff + nt], mask)
+            assert np.array_equal(vc[toff:toff + nt].cpu().numpy(), cnt)
+            ref_v, _, _ = vo.tile_layout(hz.raw_numpy(vh), wl.grid, shape, channel_major=True)   # [nt][d][128]
+            got_v = hz.raw_numpy(vt[b, toff:toff + nt]).reshape(nt, 2, d, 64)                     # [nt][2][d][64]
+            assert np.array_equal(got_v, ref_v.reshape(nt, d, 2, 64).transpose(0, 2, 1, 3))
+            qf, kf, vf = hz.to_f32_numpy(qh), hz.to_f32_numpy(kh), hz.to_f32_numpy(vh)
+            lat = []
+            for x, e in ((qf, eq), (kf, ek)):
+                lat.append(vo.mlp(vo.trippool(x, wl.grid, shape), e.w1[h], e.b1[h], e.w2[h], e.b2[h], e.relu))
+            s_ref = vo.score(lat[0], lat[1], np.float32(sscale))
+            g_s = s[b, soff:soff + nt * nt].view(nt, nt).cpu().numpy()
+            assert np.array_equal(g_s.view(np.uint32), s_ref.view(np.uint32)), (b, h)
+            sel = vo.select(s_ref, ksel)
+            r0 = b * plan.total_tiles + toff
+            lo = int(rp_np[r0])
+            assert np.all(np.diff(rp_np[r0:r0 + nt + 1]) == ksel)
+            assert np.array_equal(ci_np[lo:lo + nt * ksel].reshape(nt, ksel), sel), (b, h)
+            ref, lse_ref, _ = vo.masked_attention(qf, kf, vf, wl.grid, shape, sel, scale, queries, want_stats=True)
+            err = np.abs(hz.to_f32_numpy(out[b, h]).astype(np.float64) - ref)
+            lerr = np.abs(lse[b, h].cpu().numpy().astype(np.float64) - lse_ref)
+            _say(f"[parity] {wl.name} b{b} h{h} {shape}: max_abs {err.max():.2e} mean_abs {err.mean():.2e} "
+                 f"lse {lerr.max():.2e}")
+            assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS and lerr.max() <= 2e-2

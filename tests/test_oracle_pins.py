@@ -54,6 +54,37 @@ def test_layout_brute_force_bijection_roundtrip(grid, shape):
     assert np.array_equal(vo.tile_layout(x16, grid, shape)[0].view(np.float32), xt)
 
 
+@pytest.mark.parametrize("grid,shape", [((8, 4, 8), (8, 4, 4)), ((5, 9, 10), (2, 8, 8)), ((33, 3, 5), (32, 2, 2)),
+                                        ((3, 5, 130), (1, 1, 128))])
+def test_128_token_tiles_layout_trippool_attention(grid, shape):
+    # the paper's tile size (Sec. 4.2, B = 128): two mask words per tile, same definitions otherwise
+    n, d = int(np.prod(grid)), 6
+    x = _rand(n, d, 80)
+    xt, mask, cnt = vo.tile_layout(x, grid, shape)
+    tab = bf.slots(grid, shape)
+    ref = np.zeros_like(xt)
+    for (i, l), tok in tab.items():
+        ref[i, l] = x[tok]
+    assert xt.shape[1] == 128 and np.array_equal(xt, ref) and mask.shape == (xt.shape[0], 2)
+    for i in range(xt.shape[0]):
+        for l in range(128):
+            assert ((int(mask[i, l // 64]) >> (l % 64)) & 1) == ((i, l) in tab)
+    assert cnt.sum() == n and np.array_equal(vo.untile(xt, grid, shape), x)
+    xc, _, _ = vo.tile_layout(x, grid, shape, channel_major=True)
+    assert np.array_equal(xc, xt.transpose(0, 2, 1))
+    z = vo.trippool(x, grid, shape)
+    zr = bf.trippool64(x, grid, shape)
+    assert np.array_equal(z[:, d:], zr[:, d:].astype(np.float32))
+    assert np.allclose(z[:, :d], zr[:, :d], rtol=0, atol=128 * 2**-24 * 4)
+    nt = vo.num_tiles(grid, shape)
+    rng = np.random.default_rng(81)
+    ksel = max(1, nt // 2)
+    sel = np.stack([np.sort(rng.choice(nt, ksel, replace=False)) for _ in range(nt)]).astype(np.int32)
+    q, k, v = _rand(n, d, 82), _rand(n, d, 83), _rand(n, d, 84)
+    out = vo.masked_attention(q, k, v, grid, shape, sel, 0.4, np.arange(n))
+    assert np.allclose(out, bf.concat_tile_attention(q, k, v, grid, shape, sel, 0.4), rtol=1e-12, atol=1e-12)
+
+
 def test_layout_row_tiles_are_identity():
     # a 1x1xB tile on a grid whose width is a multiple of B keeps raster order
     grid, shape = (2, 3, 128), (1, 1, 64)
