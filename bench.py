@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--dense", action="store_true", help="also time one dense (k = N_T) attention call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
+    ap.add_argument("--tile-tokens", type=int, default=64, choices=(64, 128),
+                    help="128: the paper's tile size; every head's 64-token shape doubled along t "
+                         "(4x4x4 -> 8x4x4, 1x8x8 -> 2x8x8, 16x2x2 -> 32x2x2); same keep fraction")
     ap.add_argument("--heatmap", action="store_true",
                     help="also time the full-attention target tile scores (two dense Q K^T passes) and Recall@k")
     ap.add_argument("--unfused", action="store_true",
@@ -103,9 +106,16 @@ def main():
     wl = wlm.WORKLOADS[args.workload]
     keep = tuple(int(x) for x in args.keep.split("/")) if args.keep else None
     shapes = wlm.tile_shapes(wl)
-    kph = wlm.keep_budget(wl, keep, shapes)
+    B = args.tile_tokens
+    if B == 128:
+        shapes = shapes * np.asarray([2, 1, 1], np.int32)
+        args.unfused = True          # the descriptor-during-gather route is for 64-token tiles
+        if args.heatmap:
+            print("bench.py: --heatmap needs 64-token tiles", file=sys.stderr)
+            sys.exit(2)
     q, k, v = wlm.make_qkv(wl, dev)
-    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=B)
+    kph = wlm.keep_budget(wl, keep, shapes)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
     pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
@@ -116,9 +126,9 @@ def main():
     d, N, heads = wl.head_dim, wl.tokens, wl.heads
     tiles = np.asarray(plan.tiles, np.int64)
     pairs = int((tiles * kph).sum()) * wl.batch
-    kept_flops = pairs * 4 * 64 * 64 * d
+    kept_flops = pairs * 4 * B * B * d
     dense_flops = 4.0 * N * N * d * heads * wl.batch
-    slots = int(tiles.sum()) * 64 * wl.batch
+    slots = int(tiles.sum()) * B * wl.batch
     bytes_layout = 3 * (N * heads * wl.batch * d * es + slots * d * es)
     stat_bytes = 2 * int(tiles.sum()) * wl.batch * 3 * d * 4     # descriptors of Q and K tiles
     if args.unfused:
@@ -127,7 +137,7 @@ def main():
         bytes_layout += stat_bytes
         bytes_score = stat_bytes + int((tiles * tiles).sum()) * 4 * wl.batch
     bytes_select = int((tiles * tiles).sum()) * 4 * wl.batch + pairs * 4
-    bytes_attn_kv = pairs * 2 * 64 * d * es
+    bytes_attn_kv = pairs * 2 * B * d * es
 
     bufs = {}
     names = ("layout", "score", "select", "attn")
@@ -188,7 +198,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "grid": list(wl.grid), "tokens": N, "heads": heads, "head_dim": d,
-                   "tile_tokens": 64, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
+                   "tile_tokens": B, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
                    "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch)},
         "attn_ms_per_call": attn_ms,
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
@@ -200,7 +210,7 @@ def main():
                      "peak": PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS,
                      "unit": "TFLOP/s",
                      "frac": kept_tflops / (PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if B == 64 else None,
                      "flops_per_launch": kept_flops, "kv_tile_bytes_per_launch": bytes_attn_kv},
     }
     if not args.attn_only:
@@ -222,7 +232,7 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1)
-        padded_flops = float((tiles * tiles).sum()) * wl.batch * 4 * 64 * 64 * d
+        padded_flops = float((tiles * tiles).sum()) * wl.batch * 4 * B * B * d
         result["dense_run"] = {"attn_ms": dense_ms, "tflops_on_padded_tiles": padded_flops / (dense_ms * 1e-3) / 1e12,
                                "speedup_sparse_vs_dense": dense_ms / attn_ms,
                                "paper_context": "paper reports 10.5x self-attention / 5.1x end-to-end on NVIDIA Hopper "

@@ -55,10 +55,19 @@ typedef struct veda_plan veda_plan; /* opaque; owned by the library */
 typedef struct {
     int32_t batch, heads, head_dim;
     int32_t T, H, W;            /* latent grid; N = T*H*W tokens                            */
-    int32_t tile_tokens;        /* B; must be 64                                            */
+    int32_t tile_tokens;        /* B: 64, or 128 (the size of Sec. 4.2; bf16 only) -- see below */
     const int32_t* tile_shape;  /* host, [heads][3] = (p_t,p_h,p_w), product == B (Eq. 7)   */
     veda_dtype dtype;           /* element type of Q,K,V,O and of the tiled tensors         */
 } veda_problem;
+
+/* 128-token tiles are kept as two 64-slot halves: a tile is cut across its slowest axis of extent
+ * > 1, so slots 0-63 (raster order, time slowest) are one half and slots 64-127 the other.
+ * Everything that counts tiles (plan sizes, scores, k, CSR rows and entries) counts whole tiles;
+ *   a token-major tiled tensor is [tile][128][channel] as for any B;
+ *   a channel-major tiled tensor is [tile][half][channel][64];
+ *   valid_mask holds two u64 words per tile (word w covers slots 64w..64w+63);
+ *   veda_tile_layout needs valid_mask whenever valid_cnt is asked for;
+ *   veda_tile_layout_stats and veda_tile_heatmap are for 64-token tiles only. */
 
 /* Element strides of a token-order tensor x[b][h][n][c]; the channel stride is 1.
  * Each stride must be a multiple of 16 bytes and the base 16-byte aligned. */
@@ -94,8 +103,8 @@ size_t veda_plan_workspace_bytes(const veda_plan*, const veda_mlp* phi_q, const 
 
 /* ---- stage 1: head-aware 3D tiling (Sec. 4.2; Alg. 1 "Tiling"; Alg. 2 "Tile") ----------- */
 /* x        device, token order, strides sx, plan dtype.
- * x_tiled  device, [batch][total_tiles][64*head_dim] in `order`; padded slots are zero.
- * valid_mask device u64 [total_tiles] (bit l set iff slot l holds a real token) and
+ * x_tiled  device, [batch][total_tiles][B*head_dim] in `order`; padded slots are zero.
+ * valid_mask device u64 [total_tiles][B/64] (bit l set iff slot l holds a real token) and
  * valid_cnt  device i32 [total_tiles] (its popcount); either may be NULL.  Both depend
  * only on the geometry, not on x or the batch index. */
 veda_status veda_tile_layout(const veda_plan*, const void* x, veda_strides sx, veda_tile_order order,
