@@ -50,6 +50,7 @@ def lib():
         L.vo_dense_attention.argtypes = [vp, vp, vp, i32, i64, f64, vp, i64, vp]
         L.vo_tile_heatmap.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, f64, vp, i64, vp]
         L.vo_recall.argtypes = [vp, vp, i64, i32, vp]
+        L.vo_closed_form_latent.argtypes = [vp, i64, i32, f32, vp]
         _lib = L
     return _lib
 
@@ -197,6 +198,23 @@ def recall(sel_sp: np.ndarray, sel_fu: np.ndarray) -> float:
     out = C.c_double(0.0)
     _ok(lib().vo_recall(_p(a), _p(b), a.shape[0], a.shape[1], C.byref(out)), "recall")
     return float(out.value)
+
+
+def closed_form_latent(z: np.ndarray, lam: float) -> np.ndarray:
+    """TripPool descriptors z [n, 3d] -> y [n, 2d] = [avg | sqrt(lambda) * sqrt((max-avg)(avg-min))]."""
+    z = _f32(z)
+    n, d3 = z.shape
+    d = d3 // 3
+    y = np.empty((n, 2 * d), np.float32)
+    _ok(lib().vo_closed_form_latent(_p(z), n, d, C.c_float(np.sqrt(np.float32(lam))), _p(y)), "closed_form_latent")
+    return y
+
+
+def closed_form_scores(q, k, grid, shape, lam: float) -> np.ndarray:
+    """Weight-free tile scores: mean product plus lambda times the dispersion product, per channel."""
+    yq = closed_form_latent(trippool(q, grid, shape), lam)
+    yk = closed_form_latent(trippool(k, grid, shape), lam)
+    return score(yq, yk, np.float32(1.0))
 
 
 def tiling_search_errors(q, k, v, grid, candidates, keep, scale: float) -> np.ndarray:

@@ -463,3 +463,26 @@ int vo_recall(const int32_t* sel_sp, const int32_t* sel_fu, int64_t rows, int k,
     *recall = acc / (double)rows;
     return 0;
 }
+
+/* Weight-free scorer from the sufficient-statistics argument (App. A.3, "Reconstructing
+ * Attention via Sufficient Statistics": S ~ mean product + lambda * dispersion product, with
+ * the dispersion bounded from the extrema, Delta = sqrt((M - mu)(mu - m))).  The appendix
+ * states it for the elements of one vector; here it is read per channel over a tile's tokens,
+ * on the TripPool descriptor z = [avg | max | min] of stage 2a:
+ *     S[i][j] = sum_c mu_q[i][c] mu_k[j][c] + lambda * sum_c Delta_q[i][c] Delta_k[j][c].
+ * This function forms the 2d-long latent  y = [ mu | sqrt(lambda) * Delta ]  whose plain dot
+ * product (vo_score with scale 1) is that score.  fp32, fixed order:
+ *     Delta = sqrtf(max(0, (M - mu) * (mu - m))),  y[d + c] = root_lambda * Delta,
+ * root_lambda = sqrtf(lambda) rounded once by the caller.  z [n][3d], y [n][2d]. */
+int vo_closed_form_latent(const float* z, int64_t n, int d, float root_lambda, float* y) {
+    for (int64_t i = 0; i < n; ++i)
+        for (int c = 0; c < d; ++c) {
+            const float mu = z[i * 3 * d + c], mx = z[i * 3 * d + d + c], mn = z[i * 3 * d + 2 * d + c];
+            const float up = mx - mu, dn = mu - mn;
+            float p = up * dn;
+            p = p > 0.0f ? p : 0.0f;
+            y[i * 2 * d + c] = mu;
+            y[i * 2 * d + d + c] = root_lambda * sqrtf(p);
+        }
+    return 0;
+}

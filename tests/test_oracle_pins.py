@@ -390,6 +390,34 @@ def test_tiling_search_errors_against_brute_force_and_limits():
     assert local[0] < 1e-6 and local[1] > 1e-3 and int(np.argmin(local)) == 0
 
 
+def test_closed_form_scorer_terms():
+    grid, shape, d = (4, 8, 12), (4, 4, 4), 6
+    n = int(np.prod(grid))
+    q, k = _rand(n, d, 90), _rand(n, d, 91)
+    mem = bf.tile_members(grid, shape)
+    # lambda = 0: the score is the dot product of the tile means = the mean of q_u.k_v over the block
+    s0 = vo.closed_form_scores(q, k, grid, shape, 0.0)
+    q64, k64 = q.astype(np.float64), k.astype(np.float64)
+    for i in (0, 3, 5):
+        for j in (1, 4):
+            block = q64[mem[i]] @ k64[mem[j]].T
+            assert np.isclose(s0[i, j], block.mean(), rtol=1e-5, atol=1e-6)
+    # the lambda term is lambda * sum_c Delta_q Delta_k with Delta^2 = (max - mean)(mean - min) >= variance
+    lam = 0.7
+    s1 = vo.closed_form_scores(q, k, grid, shape, lam)
+    def delta(x, rows):
+        x = x[rows]
+        return np.sqrt((x.max(0) - x.mean(0)) * (x.mean(0) - x.min(0)))
+    for i in (0, 5):
+        for j in (2, 3):
+            want = s0[i, j] + lam * float(delta(q64, mem[i]) @ delta(k64, mem[j]))
+            assert np.isclose(s1[i, j], want, rtol=1e-5, atol=1e-6)
+            assert np.all(delta(q64, mem[i]) ** 2 >= q64[mem[i]].var(0) - 1e-12)     # Bhatia-Davis
+    # constant tiles have no dispersion: lambda does not matter
+    qc = _rand(6, d, 92)[vo.token_tile_map(grid, shape)]
+    assert np.array_equal(vo.closed_form_scores(qc, k, grid, shape, 0.0), vo.closed_form_scores(qc, k, grid, shape, 5.0))
+
+
 # ---------------------------------------------------------------- workloads feed
 def test_workload_sizes_match_the_size_table():
     w = wlm.WORKLOADS
