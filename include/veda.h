@@ -139,6 +139,19 @@ veda_status veda_tile_score_stats(const veda_plan*, const float* stats_q, const 
                                   const veda_mlp* phi_q, const veda_mlp* phi_k, float scale, float* scores,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- stage 2 without trained weights (App. A.3 "Reconstructing Attention via Sufficient
+ * Statistics": S ~ mean product + lambda * dispersion product, dispersion bounded from the
+ * extrema).  The appendix states it for the elements of one vector; it is applied here per
+ * channel to the TripPool descriptor [Avg|Max|Min] of a tile:
+ *   S[i][j] = sum_c avg_q[i][c]*avg_k[j][c] + lambda * sum_c D_q[i][c]*D_k[j][c],
+ *   D = sqrt(max(0, (Max - Avg)*(Avg - Min))),
+ * computed in fp32 as the plain dot product (one fma chain from +0 over ascending index) of the
+ * 2*head_dim-long latents [Avg | sqrtf(lambda)*D].  scores as in veda_tile_score; lambda >= 0;
+ * workspace at least batch*total_tiles*10*head_dim floats. */
+veda_status veda_tile_score_closed_form(const veda_plan*, const void* q_tiled, const void* k_tiled,
+                                        const uint64_t* valid_mask, float lambda, float* scores,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- stage 3: per-query-tile top-k (Sec. 3.1 "exactly k per row"; Sec. 4.1; Alg. 2) ------ */
 /* scores      device, as written by stage 2.
  * k_per_head  host i32 [heads], 1 <= k[h] <= N_T[h].

@@ -330,6 +330,57 @@ static veda_status check_mlp(const veda_plan* pl, const veda_mlp* m) {
     return VEDA_OK;
 }
 
+static void fill_recip(RecipTable& recip) {
+    recip.v[0] = 0.0f;
+    for (int c = 1; c <= 2 * kTile; ++c) recip.v[c] = 1.0f / (float)c;
+}
+
+// TripPool (Eq. 4) of the tiled Q and K into zq, zk.
+static void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_tiled, const uint64_t* valid_mask,
+                            float* zq, float* zk, hipStream_t s) {
+    const int d = pl->prob.head_dim;
+    const int64_t total = pl->total_tiles, rows = total * pl->prob.batch;
+    RecipTable recip;
+    fill_recip(recip);
+
+    const bool bf16 = pl->prob.dtype == VEDA_BF16;
+#define VEDA_LAUNCH_TP(E, D)                                                                               \
+    do {                                                                                                   \
+        constexpr int tpb = 256 / (D / Chunk<E>::kN);                                                      \
+        dim3 grid((unsigned)((rows + tpb - 1) / tpb), 2);                                                  \
+        if (pl->inner)                                                                                     \
+            hipLaunchKernelGGL((trippool_kernel<E, D, 2>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
+                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
+        else                                                                                               \
+            hipLaunchKernelGGL((trippool_kernel<E, D, 1>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
+                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
+    } while (0)
+    if (bf16 && d == 128) VEDA_LAUNCH_TP(uint16_t, 128);
+    else if (bf16) VEDA_LAUNCH_TP(uint16_t, 64);
+    else if (d == 128) VEDA_LAUNCH_TP(uint32_t, 128);
+    else VEDA_LAUNCH_TP(uint32_t, 64);
+#undef VEDA_LAUNCH_TP
+}
+
+// Weight-free scorer (App. A.3): latent y = [avg | root_lambda * sqrt(max(0, (max-avg)(avg-min)))] per tile,
+// whose plain dot product is the mean product plus lambda times the dispersion product.
+__global__ __launch_bounds__(256) void closed_form_latent_kernel(const float* __restrict__ zq, const float* __restrict__ zk,
+                                                                 float* __restrict__ yq, float* __restrict__ yk,
+                                                                 int64_t rows, int d, float root_lambda) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= rows * d) return;
+    const int64_t i = e / d;
+    const int c = (int)(e - i * d);
+    const float* z = (blockIdx.y == 0 ? zq : zk) + i * 3 * d;
+    float* y = (blockIdx.y == 0 ? yq : yk) + i * 2 * d;
+    const float mu = z[c], mx = z[d + c], mn = z[2 * d + c];
+    const float up = mx - mu, dn = mu - mn;
+    float p = up * dn;
+    p = p > 0.0f ? p : 0.0f;
+    y[c] = mu;
+    y[d + c] = root_lambda * sqrtf(p);
+}
+
 // Projections (Eq. 5 phi_q, phi_k) of the descriptors zq, zk into yq, yk, then the score blocks.
 static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
                                      const float* zq, const float* zk, float* yq, float* yk, float* scores,
@@ -356,11 +407,6 @@ static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q,
     return launch_status("score_kernel");
 }
 
-static void fill_recip(RecipTable& recip) {
-    recip.v[0] = 0.0f;
-    for (int c = 1; c <= 2 * kTile; ++c) recip.v[c] = 1.0f / (float)c;
-}
-
 }  // namespace veda
 
 extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
@@ -384,26 +430,7 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     float* yk = yq + rows * dp;
     hipStream_t s = (hipStream_t)stream;
 
-    RecipTable recip;
-    fill_recip(recip);
-
-    const bool bf16 = pl->prob.dtype == VEDA_BF16;
-#define VEDA_LAUNCH_TP(E, D)                                                                               \
-    do {                                                                                                   \
-        constexpr int tpb = 256 / (D / Chunk<E>::kN);                                                      \
-        dim3 grid((unsigned)((rows + tpb - 1) / tpb), 2);                                                  \
-        if (pl->inner)                                                                                     \
-            hipLaunchKernelGGL((trippool_kernel<E, D, 2>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
-                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
-        else                                                                                               \
-            hipLaunchKernelGGL((trippool_kernel<E, D, 1>), grid, dim3(256), 0, s, (const char*)q_tiled,    \
-                               (const char*)k_tiled, valid_mask, zq, zk, rows, total, recip);              \
-    } while (0)
-    if (bf16 && d == 128) VEDA_LAUNCH_TP(uint16_t, 128);
-    else if (bf16) VEDA_LAUNCH_TP(uint16_t, 64);
-    else if (d == 128) VEDA_LAUNCH_TP(uint32_t, 128);
-    else VEDA_LAUNCH_TP(uint32_t, 64);
-#undef VEDA_LAUNCH_TP
+    launch_trippool(pl, q_tiled, k_tiled, valid_mask, zq, zk, s);
     st = launch_status("trippool_kernel");
     if (st != VEDA_OK) return st;
 
@@ -427,4 +454,32 @@ extern "C" veda_status veda_tile_score_stats(const veda_plan* pl, const float* s
     float* yq = (float*)workspace;
     float* yk = yq + rows * dp;
     return project_and_score(pl, phi_q, phi_k, scale, stats_q, stats_k, yq, yk, scores, (hipStream_t)stream);
+}
+
+extern "C" veda_status veda_tile_score_closed_form(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
+                                                   const uint64_t* valid_mask, float lambda, float* scores,
+                                                   void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace veda;
+    if (!pl || !q_tiled || !k_tiled || !valid_mask || !scores) return VEDA_ERR_INVALID_ARG;
+    if (!(lambda >= 0.0f) || !(lambda < INFINITY)) return VEDA_ERR_INVALID_ARG;
+    if (!aligned16(q_tiled) || !aligned16(k_tiled) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
+    const int d = pl->prob.head_dim;
+    const int64_t rows = pl->total_tiles * pl->prob.batch;
+    if (!workspace || workspace_bytes < sizeof(float) * (size_t)rows * 10 * (size_t)d) return VEDA_ERR_WORKSPACE;
+    float* zq = (float*)workspace;
+    float* zk = zq + rows * 3 * d;
+    float* yq = zk + rows * 3 * d;
+    float* yk = yq + rows * 2 * d;
+    hipStream_t s = (hipStream_t)stream;
+    launch_trippool(pl, q_tiled, k_tiled, valid_mask, zq, zk, s);
+    veda_status st = launch_status("trippool_kernel");
+    if (st != VEDA_OK) return st;
+    dim3 lgrid((unsigned)((rows * d + 255) / 256), 2);
+    hipLaunchKernelGGL(closed_form_latent_kernel, lgrid, dim3(256), 0, s, zq, zk, yq, yk, rows, d, sqrtf(lambda));
+    st = launch_status("closed_form_latent_kernel");
+    if (st != VEDA_OK) return st;
+    dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
+    hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, 2 * d, 1.0f,
+                       pl->total_tiles, pl->score_elems);
+    return launch_status("score_kernel");
 }

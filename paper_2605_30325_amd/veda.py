@@ -26,7 +26,7 @@ EXPORTS = (
     "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
-    "veda_tile_score_stats", "veda_tile_select", "veda_sparse_attn_fwd", "veda_tile_heatmap",
+    "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_sparse_attn_fwd", "veda_tile_heatmap",
     "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
 
@@ -88,6 +88,8 @@ def load():
     L.veda_tile_score_stats.argtypes = [vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float, vp, vp,
                                         C.c_size_t, vp]
     L.veda_tile_score_stats.restype = C.c_int
+    L.veda_tile_score_closed_form.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.veda_tile_score_closed_form.restype = C.c_int
     L.veda_tile_select.argtypes = [vp, vp, C.POINTER(i32), vp, vp, vp]
     L.veda_tile_select.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
@@ -260,6 +262,21 @@ def veda_tile_score_stats(plan: Plan, stats_q, stats_k, phi_q: Mlp, phi_k: Mlp, 
                                         C.c_float(scale), _ptr(scores), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()),
            "veda_tile_score_stats")
+    return scores, workspace
+
+
+def veda_tile_score_closed_form(plan: Plan, q_tiled, k_tiled, valid_mask, lam: float,
+                                scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Stage 2 with the weight-free scorer.  Returns (scores fp32 [batch, score_elems], workspace)."""
+    dev = q_tiled.device
+    if scores is None:
+        scores = torch.empty((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(plan.batch * plan.total_tiles * 10 * plan.head_dim * 4, dtype=torch.uint8, device=dev)
+    _check(load().veda_tile_score_closed_form(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(valid_mask),
+                                              C.c_float(lam), _ptr(scores), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream()),
+           "veda_tile_score_closed_form")
     return scores, workspace
 
 

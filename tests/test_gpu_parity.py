@@ -535,3 +535,37 @@ def test_128_token_tiles_whole_path(d):
             _say(f"[parity] {wl.name} b{b} h{h} {shape}: max_abs {err.max():.2e} mean_abs {err.mean():.2e} "
                  f"lse {lerr.max():.2e}")
             assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS and lerr.max() <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,d,tile_tokens", [("bf16", 128, 64), ("f32", 64, 64), ("bf16", 64, 128)])
+def test_closed_form_scorer_bit_exact(dtype, d, tile_tokens):
+    # weight-free scores against the oracle, bit for bit, then their recall against the target scores
+    if tile_tokens == 64:
+        wl = wlm.custom_workload(f"cf_{dtype}_{d}", 4, d, dtype, (9, 18, 18), True, (25, 100), seed=91)
+        shapes = wlm.tile_shapes(wl)
+    else:
+        shapes = np.asarray([(8, 4, 4), (2, 8, 8), (1, 8, 16), (1, 1, 128)], np.int32)
+        wl = wlm.custom_workload(f"cf128_{d}", 4, d, dtype, (9, 18, 18), True, (25, 100), seed=91)
+    dev = torch.device("cuda:0")
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, d, wl.grid, shapes, wl.torch_dtype, tile_tokens=tile_tokens)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    for lam in (0.0, 0.37):
+        s, _ = veda.veda_tile_score_closed_form(plan, qt, kt, vm, lam)
+        torch.cuda.synchronize()
+        for h in range(wl.heads):
+            shape = tuple(int(x) for x in shapes[h])
+            nt, soff = plan.tiles[h], plan.score_offset[h]
+            ref = vo.closed_form_scores(hz.to_f32_numpy(q[0, h]), hz.to_f32_numpy(k[0, h]), wl.grid, shape, lam)
+            got = s[0, soff:soff + nt * nt].view(nt, nt).cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (lam, h)
+    if tile_tokens == 64:
+        kph = wlm.keep_budget(wl, None, shapes)
+        heat = veda.veda_tile_heatmap(plan, qt, kt, vm, 1.0 / math.sqrt(d))
+        _, ci_t = veda.veda_tile_select(plan, heat, kph)
+        _, ci_c = veda.veda_tile_select(plan, s, kph)
+        rec = veda.veda_tile_recall(plan, kph, ci_c, ci_t)
+        torch.cuda.synchronize()
+        _say(f"[parity] {wl.name}: recall of the closed-form scorer against the target scores {rec.cpu().numpy().round(3).tolist()}")
+        assert bool((rec > 0.25).all())      # well above the 0.25 keep fraction a blind scorer would get
