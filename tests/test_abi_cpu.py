@@ -51,8 +51,12 @@ def test_plan_create_rejects_bad_problems(lib):
     for p, keep in bad:
         assert lib.veda_plan_create(C.byref(p), C.byref(out)) == veda.VEDA_ERR_INVALID_ARG
         assert out.value is None
-    p, keep = _problem([[4, 4, 8], [4, 4, 8]], tile_tokens=128)
+    p, keep = _problem([[4, 4, 8], [4, 4, 8]], tile_tokens=128)            # 128-token tiles are bf16 only
     assert lib.veda_plan_create(C.byref(p), C.byref(out)) == veda.VEDA_ERR_UNSUPPORTED
+    p, keep = _problem([[4, 8, 8], [4, 8, 8]], tile_tokens=256, dtype=1)
+    assert lib.veda_plan_create(C.byref(p), C.byref(out)) == veda.VEDA_ERR_UNSUPPORTED
+    p, keep = _problem([[4, 4, 8], [4, 4, 4]], tile_tokens=128, dtype=1)   # product != B for head 1
+    assert lib.veda_plan_create(C.byref(p), C.byref(out)) == veda.VEDA_ERR_INVALID_ARG
     p, keep = _problem([[4, 4, 4], [4, 4, 4]], head_dim=96)
     assert lib.veda_plan_create(C.byref(p), C.byref(out)) == veda.VEDA_ERR_UNSUPPORTED
     assert lib.veda_plan_create(None, C.byref(out)) == veda.VEDA_ERR_INVALID_ARG
@@ -64,5 +68,11 @@ def test_stage_calls_reject_null_plan(lib):
     assert lib.veda_tile_score(None, None, None, None, None, None, 0.125, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_select(None, None, None, None, None, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_sparse_attn_fwd(None, None, None, None, None, None, None, 0.125, None, s, None, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_layout_stats(None, None, s, None, None, None, None, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_score_stats(None, None, None, None, None, 0.125, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_score_closed_form(None, None, None, None, 0.5, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_heatmap(None, None, None, None, 0.125, None, 0, None, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_recall(None, None, None, None, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_output_sqerr(None, None, s, None, s, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_plan_tiles(None, 0) == -1 and lib.veda_plan_total_tiles(None) == -1
     lib.veda_plan_destroy(None)
