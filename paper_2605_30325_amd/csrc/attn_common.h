@@ -46,10 +46,28 @@ __device__ inline bool xcd_work(const int32_t* __restrict__ xcd_cum, const HeadG
     if (local >= cum[n_heads]) return false;
     int h = 0;
     while (local >= cum[h + 1]) ++h;
-    const int n = (heads[h].n_tiles + unit - 1) / unit;
+    const int n = unit == 2 ? heads[h].n_pairs : heads[h].n_tiles;
     head = h;
     item = x * (n / kXcd) + (x < n % kXcd ? x : n % kXcd) + (local - cum[h]);
     return true;
+}
+
+// Work item p of a head -> its query tiles: A always, B = A's neighbour along g.pair_ax if it
+// exists (the last layer of an odd-sized axis has none).
+__device__ inline void pair_tiles(const HeadGeom& g, int p, int& qiA, int& qiB, bool& hasB) {
+    if (g.pair_ax == 3) {            // halves of a 128-token tile
+        qiA = 2 * p; qiB = qiA + 1; hasB = true;
+    } else if (g.pair_ax == 2) {
+        const int half = (g.nw + 1) / 2, tw2 = p % half, rest = p / half;
+        qiA = rest * g.nw + 2 * tw2; qiB = qiA + 1; hasB = 2 * tw2 + 1 < g.nw;
+    } else if (g.pair_ax == 1) {
+        const int half = (g.nh + 1) / 2, tw = p % g.nw, th2 = (p / g.nw) % half, tt = p / (g.nw * half);
+        qiA = (tt * g.nh + 2 * th2) * g.nw + tw; qiB = qiA + g.nw; hasB = 2 * th2 + 1 < g.nh;
+    } else {
+        const int plane = g.nh * g.nw, rest = p % plane, tt2 = p / plane;
+        qiA = 2 * tt2 * plane + rest; qiB = qiA + plane; hasB = 2 * tt2 + 1 < g.nt;
+    }
+    if (!hasB) qiB = qiA;
 }
 
 __device__ inline int rho(int m) {  // swap bits 2 and 3

@@ -3,11 +3,12 @@
 // A compute unit can pull K/V tiles from L2 into LDS at 64 bytes per clock at most, and a kept
 // tile pair needs 32 KB of them for 512 matrix-pipe cycles of work: with one query tile per
 // workgroup the loads, not the matrix cores, set the pace.  Neighbouring query tiles keep
-// largely the same key tiles, so here one workgroup owns TWO adjacent query tiles and walks
-// the union of their two kept lists: a key tile kept by both is loaded once and used twice.
+// largely the same key tiles, so here one workgroup owns TWO neighbouring query tiles (partners
+// along the axis in which the head's tile shape is thinnest: pair_tiles()) and walks the union
+// of their two kept lists: a key tile kept by both is loaded once and used twice.
 //
-// Four wavefronts: waves 0,1 hold rows 0-31 / 32-63 of query tile A = 2p, waves 2,3 those of
-// tile B = 2p+1.  Every wave attends to all 64 slots of a key tile, so it needs no merge with
+// Four wavefronts: waves 0,1 hold rows 0-31 / 32-63 of query tile A, waves 2,3 those of its
+// partner B.  Every wave attends to all 64 slots of a key tile, so it needs no merge with
 // another wave at the end.  A wave whose query tile does not keep the current key tile skips
 // the step and only meets the others at the barrier; the matrix cores it leaves idle go to the
 // second workgroup resident on the compute unit.
@@ -194,8 +195,8 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
 // workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, lse_s after it.
 template <int D>
 __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnArgs& a, const HeadGeom& hg, char* smem,
-                                            int head, int qiA, bool hasB, int64_t b, int tid, int which, int r,
-                                            int lq, int hh) {
+                                            int head, int qiA, int qiB, bool hasB, int64_t b, int tid, int which,
+                                            int r, int lq, int hh) {
     constexpr int kRowB = D * 2, kKChunks = kRowB / 16;
     const float l_all = st.l_run + __shfl_xor(st.l_run, 32);
     const float inv = l_all > 0.0f ? 1.0f / l_all : 0.0f;
@@ -222,13 +223,13 @@ __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnAr
     const int n_tiles = hasB ? 2 : 1;
     for (int cid = tid; cid < n_tiles * kTile * kKChunks; cid += 256) {
         const int row = cid / kKChunks, ch = cid % kKChunks;
-        const int n = slot_token(hg, qiA + row / kTile, row % kTile, a.T, a.H, a.W);
+        const int n = slot_token(hg, row / kTile ? qiB : qiA, row % kTile, a.T, a.H, a.W);
         if (n >= 0)
             *reinterpret_cast<uint4*>(ob + (int64_t)n * a.so_n + ch * 16) =
                 *reinterpret_cast<const uint4*>(obuf + row * kRowB + ch * 16);
     }
     if (a.lse && tid < n_tiles * kTile) {
-        const int n = slot_token(hg, qiA + tid / kTile, tid % kTile, a.T, a.H, a.W);
+        const int n = slot_token(hg, tid / kTile ? qiB : qiA, tid % kTile, a.T, a.H, a.W);
         if (n >= 0) a.lse[(b * a.n_heads + head) * a.tokens + n] = lse_s[tid];
     }
 }
@@ -263,21 +264,21 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, 2, head, pair)) return;
     const HeadGeom hg = a.heads[head];
     const int64_t b = blockIdx.y;
-    const int qiA = 2 * pair;
-    const bool hasB = kGrouped || qiA + 1 < hg.n_tiles;
-    const int qi = (which == 0 || hasB) ? qiA + which : qiA;
-    const int64_t rowA = kGrouped ? b * (a.total_tiles / 2) + hg.tile_off / 2 + pair
-                                  : b * a.total_tiles + hg.tile_off + qiA;
-    const int begA = a.row_ptr[rowA], endA = a.row_ptr[rowA + 1];
-    const int nA = endA - begA;
-    const int nB = kGrouped ? nA : (hasB ? a.row_ptr[rowA + 2] - endA : 0);
+    int qiA, qiB;
+    bool hasB;
+    pair_tiles(hg, pair, qiA, qiB, hasB);
+    const int qi = which ? qiB : qiA;
+    const int64_t row0 = kGrouped ? b * (a.total_tiles / 2) + hg.tile_off / 2 : b * a.total_tiles + hg.tile_off;
+    const int64_t rowA = row0 + (kGrouped ? pair : qiA), rowB = row0 + (kGrouped ? pair : qiB);
+    const int begA = a.row_ptr[rowA], nA = a.row_ptr[rowA + 1] - begA;
+    const int begB = a.row_ptr[rowB], nB = hasB ? a.row_ptr[rowB + 1] - begB : 0;
     // The kept lists and the validity masks are read-only for the whole launch and indexed
     // uniformly: reading them through the constant address space makes them scalar loads, so
     // no vector-memory counter waits of the compiler's own end up inside the main loop.
     typedef const __attribute__((address_space(4))) int32_t* const_i32_t;
     typedef const __attribute__((address_space(4))) uint64_t* const_u64_t;
     const const_i32_t colsA = (const_i32_t)(uintptr_t)(a.col_idx + begA);
-    const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + ((hasB && !kGrouped) ? endA : begA));
+    const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + begB);
     const const_u64_t vmask = (const_u64_t)(uintptr_t)(a.valid_mask + hg.tile_off);
     const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
     const char* kt = a.k + head_tile0 * kKBytes;
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
 #undef VEDA_LOAD_KV
 #undef VEDA_LOADS_DONE_BARRIER
 
-    finish_pair<D>(st, a, hg, smem, head, qiA, hasB, b, tid, which, r, lq, hh);
+    finish_pair<D>(st, a, hg, smem, head, qiA, qiB, hasB, b, tid, which, r, lq, hh);
 }
 
 veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s) {

@@ -85,26 +85,25 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
     const int lq = lane & 31, hh = lane >> 5;
 
     // work item: a pair of adjacent query tiles of one head
-    int head, qiA;
+    int head, qiA, qiB;
     bool hasB;
     if (a.query_tiles) {
         // listed tiles are processed one per workgroup (tile B absent)
         if ((int64_t)blockIdx.x >= a.n_query_tiles) return;
         const int g = a.query_tiles[blockIdx.x];
         head = a.tile_head[g];
-        qiA = g - a.heads[head].tile_off;
+        qiA = qiB = g - a.heads[head].tile_off;
         hasB = false;
     } else {
         int pair;
         if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, 2, head, pair)) return;
-        qiA = 2 * pair;
-        hasB = qiA + 1 < a.heads[head].n_tiles;
+        pair_tiles(a.heads[head], pair, qiA, qiB, hasB);
     }
     const HeadGeom hg = a.heads[head];
     const int n = hg.n_tiles;
     const int64_t b = blockIdx.y;
     const bool active = which == 0 || hasB;
-    const int qi = active ? qiA + which : qiA;
+    const int qi = which ? qiB : qiA;
     const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
     const char* kt = a.k + head_tile0 * kKBytes;
     typedef const __attribute__((address_space(4))) uint64_t* const_u64_t;
@@ -181,7 +180,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         if (j + 1 < n) VEDA_LOAD_K(j + 1, (j + 1) & 1);
         // the block maxima of step j-1 were published by that step's barrier
         if (j > 0 && tid < 2 && (tid == 0 || hasB))
-            hrow[(int64_t)(qiA + tid) * n + (j - 1)] = fmaxf(part[(j - 1) & 1][2 * tid], part[(j - 1) & 1][2 * tid + 1]);
+            hrow[(int64_t)(tid ? qiB : qiA) * n + (j - 1)] = fmaxf(part[(j - 1) & 1][2 * tid], part[(j - 1) & 1][2 * tid + 1]);
         const uint64_t vm = vmask[j];
         float blockmax = 0.0f;
         if (active) {
@@ -200,7 +199,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         VEDA_LOADS_DONE_BARRIER();
     }
     if (tid < 2 && (tid == 0 || hasB))
-        hrow[(int64_t)(qiA + tid) * n + (n - 1)] = fmaxf(part[(n - 1) & 1][2 * tid], part[(n - 1) & 1][2 * tid + 1]);
+        hrow[(int64_t)(tid ? qiB : qiA) * n + (n - 1)] = fmaxf(part[(n - 1) & 1][2 * tid], part[(n - 1) & 1][2 * tid + 1]);
 #undef VEDA_LOAD_K
 #undef VEDA_LOADS_DONE_BARRIER
 #undef VEDA_SWAP32

@@ -1,5 +1,6 @@
 // Plan object: validates a problem, derives every head's ceil-padded tile grid (Sec. 3.1 tiles
 // of size B; Sec. 4.2 per-head shapes from Omega, Eq. 7) and uploads the per-head table.
+#include <algorithm>
 #include <new>
 
 #include "veda_internal.h"
@@ -60,6 +61,30 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
         g.nw = (p->W + g.ow - 1) / g.ow;
         const int64_t n = (int64_t)grp * g.nt * g.nh * g.nw;
         g.n_tiles = (int32_t)n;
+        if (grp == 2) {
+            g.pair_ax = 3;
+            g.n_pairs = (int32_t)(n / 2);
+        } else {
+            // Expected K/V loads per kept tile pair if partners are taken along axis a: neighbours
+            // along the thinnest extent share the most (about 0.60 of the loads of two separate
+            // walks against 0.68 along a thicker one, measured on the synthetic workloads), and an
+            // odd tile count leaves 1/cnt of the tiles without a partner (no sharing, half a
+            // workgroup idle).  Smallest estimate wins; ties go to w, then h.
+            const int ext[3] = {g.pt, g.ph, g.pw}, cnt[3] = {g.nt, g.nh, g.nw};
+            const int thin = std::min(ext[0], std::min(ext[1], ext[2]));
+            int ax = -1;
+            double best = 0.0;
+            for (int a = 2; a >= 0; --a) {
+                if (cnt[a] < 2) continue;
+                const double alone = cnt[a] % 2 ? 1.0 / cnt[a] : 0.0;
+                const double cost = (1.0 - alone) * (ext[a] == thin ? 0.60 : 0.68) + alone;
+                if (ax < 0 || cost < best - 1e-12) { ax = a; best = cost; }
+            }
+            g.pair_ax = ax < 0 ? 2 : ax;
+            int64_t items = 1;
+            for (int a = 0; a < 3; ++a) items *= a == g.pair_ax ? (cnt[a] + 1) / 2 : cnt[a];
+            g.n_pairs = (int32_t)items;
+        }
         g.tile_off = (int32_t)toff;
         g.score_off = soff;
         g.score_blk_dim = (int32_t)((n + 127) / 128);
@@ -92,7 +117,7 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
             int32_t acc = 0;
             for (int h = 0; h < p->heads; ++h) {
                 cum[(size_t)x * (p->heads + 1) + h] = acc;
-                const int32_t n = (pl->heads[h].n_tiles + unit - 1) / unit;
+                const int32_t n = unit == 2 ? pl->heads[h].n_pairs : pl->heads[h].n_tiles;
                 acc += n / veda::kXcd + (x < n % veda::kXcd ? 1 : 0);
             }
             cum[(size_t)x * (p->heads + 1) + p->heads] = acc;

@@ -35,6 +35,12 @@ struct HeadGeom {
     int32_t ot, oh, ow;      // extents of a whole tile
     int32_t ht, hh, hw;      // token offset of the second half inside a whole tile
     int32_t grp;             // 64-slot tiles per whole tile: 1 or 2
+    // Query tiles are processed two at a time by the bf16 attention and heat-map kernels.  Partners
+    // are neighbours along pair_ax (0 = t, 1 = h, 2 = w: the axis along which a tile is thinnest, so
+    // its neighbour is the closest one and keeps the most similar key tiles); a last layer without a
+    // partner is processed alone.  pair_ax = 3: the two halves of a 128-token tile.
+    int32_t pair_ax;
+    int32_t n_pairs;         // work items (pairs and partnerless tiles) of this head
 };
 
 #if defined(__HIPCC__)
@@ -95,7 +101,7 @@ struct veda_plan {
     // d_xcd_cum[x*(heads+1) + h] = number of query tiles die x owns in heads < h.
     int32_t* d_xcd_cum = nullptr;       // device [8][heads+1]
     int32_t xcd_max_tiles = 0;          // max over dies of the die's total
-    // The same split over PAIRS of adjacent query tiles (2p, 2p+1), for the pair kernel.
+    // The same split over the pair work items of the heads (HeadGeom::n_pairs), for the pair kernels.
     int32_t* d_xcd_cum_pair = nullptr;  // device [8][heads+1]
     int32_t xcd_max_pairs = 0;
     int elem_size() const { return prob.dtype == VEDA_BF16 ? 2 : 4; }
