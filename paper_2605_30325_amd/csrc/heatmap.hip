@@ -69,7 +69,10 @@ __device__ __forceinline__ void heat_logits(f32x16 (&s)[2], const bf16x8 (&qf)[D
     }
 }
 
-template <int D>
+// kGrouped: 128-token tiles.  The geometry in `a` is that of the 64-slot halves; the workgroup's
+// pair is one whole query tile, and the block maximum of a whole (query tile, key tile) pair is
+// the maximum over its four half-tile blocks: both halves of the query tile, two consecutive steps.
+template <int D, bool kGrouped>
 __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
     constexpr int kRowB = D * 2, kKBytes = kTile * kRowB, kKChunks = kRowB / 16;
     constexpr int kLoads = kKBytes / 1024 / 4;   // direct-load instructions per wave per K tile
@@ -91,9 +94,16 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         // listed tiles are processed one per workgroup (tile B absent)
         if ((int64_t)blockIdx.x >= a.n_query_tiles) return;
         const int g = a.query_tiles[blockIdx.x];
-        head = a.tile_head[g];
-        qiA = qiB = g - a.heads[head].tile_off;
-        hasB = false;
+        if (kGrouped) {   // g counts whole tiles
+            head = a.tile_head[2 * g];
+            qiA = 2 * g - a.heads[head].tile_off;
+            qiB = qiA + 1;
+            hasB = true;
+        } else {
+            head = a.tile_head[g];
+            qiA = qiB = g - a.heads[head].tile_off;
+            hasB = false;
+        }
     } else {
         int pair;
         if (!xcd_work(a.xcd_cum, a.heads, a.n_heads, 2, head, pair)) return;
@@ -173,14 +183,26 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
     const float inv_l = 1.0f / l;
 
     // ---- pass 2: block maxima of exp2(s - m) / l ----
-    float* hrow = a.heat + b * a.score_elems + hg.score_off;
+    // whole-tile score blocks hold a quarter of the half-tile ones
+    float* hrow = a.heat + b * a.score_elems + (kGrouped ? hg.score_off / 4 : hg.score_off);
+    float even_step = 0.0f;   // grouped: maximum of the even step of the current whole key tile
+    // publishes the block maxima of step jj (written before that step's barrier)
+    auto publish = [&](int jj) {
+        if (kGrouped) {
+            if (tid == 0) {
+                const float v = fmaxf(fmaxf(part[jj & 1][0], part[jj & 1][1]), fmaxf(part[jj & 1][2], part[jj & 1][3]));
+                if (jj & 1) hrow[(int64_t)(qiA >> 1) * (n >> 1) + (jj >> 1)] = fmaxf(even_step, v);
+                else even_step = v;
+            }
+        } else if (tid < 2 && (tid == 0 || hasB)) {
+            hrow[(int64_t)(tid ? qiB : qiA) * n + jj] = fmaxf(part[jj & 1][2 * tid], part[jj & 1][2 * tid + 1]);
+        }
+    };
     VEDA_LOAD_K(0, 0);
     VEDA_LOADS_DONE_BARRIER();
     for (int j = 0; j < n; ++j) {
         if (j + 1 < n) VEDA_LOAD_K(j + 1, (j + 1) & 1);
-        // the block maxima of step j-1 were published by that step's barrier
-        if (j > 0 && tid < 2 && (tid == 0 || hasB))
-            hrow[(int64_t)(tid ? qiB : qiA) * n + (j - 1)] = fmaxf(part[(j - 1) & 1][2 * tid], part[(j - 1) & 1][2 * tid + 1]);
+        if (j > 0) publish(j - 1);
         const uint64_t vm = vmask[j];
         float blockmax = 0.0f;
         if (active) {
@@ -198,8 +220,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         if (lane == 0) part[j & 1][wave] = blockmax;
         VEDA_LOADS_DONE_BARRIER();
     }
-    if (tid < 2 && (tid == 0 || hasB))
-        hrow[(int64_t)(tid ? qiB : qiA) * n + (n - 1)] = fmaxf(part[(n - 1) & 1][2 * tid], part[(n - 1) & 1][2 * tid + 1]);
+    publish(n - 1);
 #undef VEDA_LOAD_K
 #undef VEDA_LOADS_DONE_BARRIER
 #undef VEDA_SWAP32
@@ -342,33 +363,39 @@ extern "C" veda_status veda_tile_heatmap(const veda_plan* pl, const void* q_tile
                                          void* stream) {
     using namespace veda;
     if (!pl || !q_tiled || !k_tiled || !valid_mask || !heat) return VEDA_ERR_INVALID_ARG;
-    if (pl->inner) return VEDA_ERR_UNSUPPORTED;   // 64-token tiles only
     if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return VEDA_ERR_INVALID_ARG;
     if (query_tiles ? (n_query_tiles < 1 || n_query_tiles > pl->total_tiles) : n_query_tiles != 0)
         return VEDA_ERR_INVALID_ARG;
     if (!aligned16(q_tiled) || !aligned16(k_tiled)) return VEDA_ERR_UNSUPPORTED;
     const int d = pl->prob.head_dim;
     const bool bf16 = pl->prob.dtype == VEDA_BF16;
+    // 128-token tiles (bf16 only): the kernel walks their 64-slot halves, heat counts whole tiles
+    const veda_plan* ip = pl->inner ? pl->inner : pl;
     HeatArgs a;
-    a.heads = pl->d_heads;
-    a.tile_head = pl->d_tile_head;
-    a.xcd_cum = bf16 ? pl->d_xcd_cum_pair : pl->d_xcd_cum;
+    a.heads = ip->d_heads;
+    a.tile_head = ip->d_tile_head;
+    a.xcd_cum = bf16 ? ip->d_xcd_cum_pair : ip->d_xcd_cum;
     a.query_tiles = query_tiles;
     a.n_query_tiles = query_tiles ? n_query_tiles : 0;
     a.q = (const char*)q_tiled; a.k = (const char*)k_tiled;
     a.valid_mask = valid_mask;
     a.heat = heat;
-    a.total_tiles = pl->total_tiles;
+    a.total_tiles = ip->total_tiles;
     a.score_elems = pl->score_elems;
     a.n_heads = pl->prob.heads;
     a.scale_log2 = softmax_scale * kLog2e;
     hipStream_t s = (hipStream_t)stream;
-    const int64_t items = query_tiles ? n_query_tiles : (int64_t)kXcd * (bf16 ? pl->xcd_max_pairs : pl->xcd_max_tiles);
+    const int64_t items = query_tiles ? n_query_tiles : (int64_t)kXcd * (bf16 ? ip->xcd_max_pairs : ip->xcd_max_tiles);
     dim3 grid((unsigned)items, (unsigned)pl->prob.batch), block(256);
     if (bf16) {
         const size_t smem = (size_t)2 * kTile * d * 2 + 2 * 4 * sizeof(float);
-        if (d == 128) hipLaunchKernelGGL(tile_heatmap_bf16_kernel<128>, grid, block, smem, s, a);
-        else hipLaunchKernelGGL(tile_heatmap_bf16_kernel<64>, grid, block, smem, s, a);
+        if (pl->inner) {
+            if (d == 128) hipLaunchKernelGGL((tile_heatmap_bf16_kernel<128, true>), grid, block, smem, s, a);
+            else hipLaunchKernelGGL((tile_heatmap_bf16_kernel<64, true>), grid, block, smem, s, a);
+        } else {
+            if (d == 128) hipLaunchKernelGGL((tile_heatmap_bf16_kernel<128, false>), grid, block, smem, s, a);
+            else hipLaunchKernelGGL((tile_heatmap_bf16_kernel<64, false>), grid, block, smem, s, a);
+        }
     } else {
         if (d == 128) hipLaunchKernelGGL(tile_heatmap_f32_kernel<128>, grid, block, 0, s, a, softmax_scale);
         else hipLaunchKernelGGL(tile_heatmap_f32_kernel<64>, grid, block, 0, s, a, softmax_scale);

@@ -499,8 +499,12 @@ def test_128_token_tiles_whole_path(d):
     out, lse = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, scale, out=out, want_lse=True)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
-    with pytest.raises(veda.VedaError):
-        veda.veda_tile_heatmap(plan, qt, kt, vm, scale)      # 64-token tiles only
+    # target tile scores over whole 128-token tiles, all rows and then a subset
+    heat = veda.veda_tile_heatmap(plan, qt, kt, vm, scale)
+    some = np.asarray(sorted({0, plan.total_tiles - 1, plan.tile_offset[2] + 1}), np.int32)
+    part = torch.full_like(heat, -7.0)
+    veda.veda_tile_heatmap(plan, qt, kt, vm, scale, torch.as_tensor(some).to(dev), part)
+    torch.cuda.synchronize()
     rp_np, ci_np = rp.cpu().numpy(), ci.cpu().numpy()
     vm_np = vm.cpu().numpy().view(np.uint64).reshape(-1, 2)
     queries = np.arange(wl.tokens)
@@ -532,9 +536,17 @@ def test_128_token_tiles_whole_path(d):
             ref, lse_ref, _ = vo.masked_attention(qf, kf, vf, wl.grid, shape, sel, scale, queries, want_stats=True)
             err = np.abs(hz.to_f32_numpy(out[b, h]).astype(np.float64) - ref)
             lerr = np.abs(lse[b, h].cpu().numpy().astype(np.float64) - lse_ref)
+            h_ref = vo.tile_heatmap(qf, kf, wl.grid, shape, scale)
+            h_got = heat[b, soff:soff + nt * nt].view(nt, nt).cpu().numpy().astype(np.float64)
+            rel = (np.abs(h_got - h_ref) / h_ref).max()
+            p_got = part[b, soff:soff + nt * nt].view(nt, nt).cpu().numpy()
+            listed = np.asarray([g - toff for g in some if toff <= g < toff + nt], np.int64)
+            assert np.array_equal(p_got[listed], heat[b, soff:soff + nt * nt].view(nt, nt).cpu().numpy()[listed])
+            assert np.all(np.delete(p_got, listed, axis=0) == -7.0)
             _say(f"[parity] {wl.name} b{b} h{h} {shape}: max_abs {err.max():.2e} mean_abs {err.mean():.2e} "
-                 f"lse {lerr.max():.2e}")
+                 f"lse {lerr.max():.2e} heat rel {rel:.2e}")
             assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS and lerr.max() <= 2e-2
+            assert rel <= 2e-4
 
 
 @pytest.mark.parametrize("dtype,d,tile_tokens", [("bf16", 128, 64), ("f32", 64, 64), ("bf16", 64, 128)])
