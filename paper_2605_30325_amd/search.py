@@ -37,8 +37,9 @@ def _dense_output(plan: veda.Plan, qt, kt, vt, vm, softmax_scale: float) -> torc
 
 def tiling_search(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, grid: Sequence[int],
                   candidates: Sequence[Sequence[int]], keep: Tuple[int, int],
-                  softmax_scale: Optional[float] = None):
-    """q, k, v: [samples, heads, N, d] device tensors (bf16 or fp32), N = T*H*W of `grid`.
+                  softmax_scale: Optional[float] = None, tile_tokens: int = 64):
+    """q, k, v: [samples, heads, N, d] device tensors (bf16 or fp32), N = T*H*W of `grid`;
+    candidates: tile shapes whose product is tile_tokens (64, or 128 for bf16).
     Returns (best [heads, 3] int32 tile shapes, errors float64 [heads, len(candidates)])."""
     samples, heads, n_tok, d = q.shape
     scale = 1.0 / math.sqrt(d) if softmax_scale is None else float(softmax_scale)
@@ -46,7 +47,7 @@ def tiling_search(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, grid: Seque
     o_full = None
     for c, shape in enumerate(candidates):
         shapes = np.tile(np.asarray(shape, np.int32), (heads, 1))
-        plan = veda.Plan(samples, heads, d, grid, shapes, q.dtype)
+        plan = veda.Plan(samples, heads, d, grid, shapes, q.dtype, tile_tokens=tile_tokens)
         qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
         kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
         vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, want_mask=False)

@@ -412,15 +412,15 @@ def test_target_heatmap_and_recall(dtype, d):
     assert bool((same == 1.0).all())
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_tiling_search_errors_and_choice(dtype):
+@pytest.mark.parametrize("dtype,tile_tokens", [("f32", 64), ("bf16", 64), ("bf16", 128)])
+def test_tiling_search_errors_and_choice(dtype, tile_tokens):
     # Alg. 1 on synthetic calibration tensors: error table against the oracle, same argmin where the
     # oracle's margin is clear.  Head 0 attends within its own frame only, so the frame-shaped
     # tiling must win it by a wide margin.
     from paper_2605_30325_amd import search
     grid, d, heads, samples = (8, 12, 16), 64, 3, 2
     n = int(np.prod(grid))
-    cands = [(4, 4, 4), (1, 8, 8), (16, 2, 2)]
+    cands = [(4, 4, 4), (1, 8, 8), (16, 2, 2)] if tile_tokens == 64 else [(8, 4, 4), (1, 8, 16), (32, 2, 2)]
     wl = wlm.custom_workload(f"search_{dtype}", heads, d, dtype, grid, False, (25, 100), seed=71, batch=samples)
     dev = torch.device("cuda:0")
     q, k, v = wlm.make_qkv(wl, dev)
@@ -430,7 +430,7 @@ def test_tiling_search_errors_and_choice(dtype):
     q[:, 0] = onehot.to(q.dtype)
     k[:, 0] = onehot.to(k.dtype)
     scale = 1.0 / math.sqrt(d)
-    best, table = search.tiling_search(q, k, v, grid, cands, (25, 100), scale)
+    best, table = search.tiling_search(q, k, v, grid, cands, (25, 100), scale, tile_tokens=tile_tokens)
     torch.cuda.synchronize()
     ref = np.zeros_like(table)
     for h in range(heads):
@@ -441,7 +441,7 @@ def test_tiling_search_errors_and_choice(dtype):
     # bf16 outputs carry 2^-9 relative rounding on both tensors: an absolute floor per table entry
     floor = samples * n * d * (2.0 ** -8 * 0.5) ** 2 if dtype == "bf16" else 1e-6
     assert np.all(np.abs(table - ref) <= 0.03 * ref + floor), (table, ref)
-    assert tuple(best[0]) == (1, 8, 8)
+    assert tuple(best[0]) == cands[1]          # the frame-shaped tiling
     for h in range(heads):
         order = np.sort(ref[h])
         if order[1] - order[0] > 0.1 * order[1] + 2 * floor:
