@@ -45,6 +45,7 @@ constexpr float kPairSlack = 8.0f;   // log2 units a row maximum may outgrow the
 // after the final division by l.
 template <int D> struct PairState {
     f32x16 o[D / 32];
+    f32x16 start;        // -ref in every register: the C operand of the first MFMA of an S^T block
     bf16x8 qf[D / 16];
     float ref, l_run;
     bool started;
@@ -56,12 +57,15 @@ template <int D> struct PairState {
 // V^T fragment (channel block nb, key step kk of 16 slots) at (v0 ^ (kk << 5)) + nb * 4096.
 struct PairAddr {
     uint32_t k0, v0;
-    int swap_addr;   // ds_bpermute address of lane ^ 32
     int hh;
 };
 
-__device__ __forceinline__ float swap32(float x, int swap_addr) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(swap_addr, __builtin_bit_cast(int, x)));
+// max(x, x of lane ^ 32) without a trip through LDS: the swap exchanges lanes 32-63 of its first
+// operand with lanes 0-31 of its second, leaving (low half, low half) and (high half, high half).
+__device__ __forceinline__ float max_with_other_half(float x) {
+    float lo = x, hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+    return fmaxf(lo, hi);
 }
 
 // One key tile for one wave; slot = LDS byte offset of the (K tile, V^T tile) pair.
@@ -83,11 +87,6 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
     bf16x8 fr[NF];
     bf16x8 pf[4];     // P^T operand of key step kk = 2c + s2: registers 8*s2..8*s2+7 of block c
     f32x16 s[2];
-    const float init = -st.ref;
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[c][i] = init;
 #pragma unroll
     for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f);
     __builtin_amdgcn_sched_barrier(0);
@@ -95,7 +94,7 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
 #pragma unroll
     for (int f = 0; f < G; ++f) {
         fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], s[0], 0, 0, 0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], f == 0 ? st.start : s[0], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
     // S^T block 1; the row maximum of block 0 rides along from the third MFMA on (block 0's
@@ -104,7 +103,7 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
 #pragma unroll
     for (int f = G; f < 2 * G; ++f) {
         fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], s[1], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], f == G ? st.start : s[1], 0, 0, 0);
         if (f - G >= 2) {
             constexpr int per = 16 / (G - 2) + (16 % (G - 2) ? 1 : 0);
 #pragma unroll
@@ -134,7 +133,7 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
             }
         }
     }
-    mx = fmaxf(mx, swap32(mx, fa.swap_addr));   // row maximum relative to the reference
+    mx = max_with_other_half(mx);   // row maximum relative to the reference
     if (!st.started || __any(mx > kPairSlack)) {
         // Move the reference of every row whose maximum is above it (first step: to the
         // maximum itself, up or down).
@@ -143,6 +142,8 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
         const float alpha = st.started ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // O = l = 0 before
         st.ref += delta;
         st.l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.start[i] = -st.ref;
 #pragma unroll
         for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -299,6 +300,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.o[nb][i] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.start[i] = 0.0f;
     st.ref = st.l_run = 0.0f;
     st.started = false;
 
@@ -335,7 +338,6 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
 
     PairAddr fa;
     fa.hh = hh;
-    fa.swap_addr = (lane ^ 32) << 2;
     fa.k0 = smem_base + rho(lq) * kRowB + ((hh ^ (lq & (kKChunks - 1))) << 4);
     fa.v0 = smem_base + kKBytes + lq * 128 + ((hh ^ (((lq >> 1) & 7) ^ ((lq & 1) << 2))) << 4);
 
