@@ -86,6 +86,25 @@ __device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base
                  : "memory", "m0");
 }
 
+// x of this lane and x of lane ^ 32, without a trip through LDS: the swap exchanges lanes 32-63
+// of its first operand with lanes 0-31 of its second, leaving (low half, low half) in one
+// register and (high half, high half) in the other.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float max_with_other_half(float x) {
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return lo + hi;
+}
+
 // Launches the query-tile-pair bf16 kernel (attn_pair.hip) on plan pl's geometry; a.xcd_cum must be
 // its pair table.  grouped: pl is the inner plan of 128-token tiles and the CSR counts whole tiles.
 veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s);

@@ -60,14 +60,6 @@ struct PairAddr {
     int hh;
 };
 
-// max(x, x of lane ^ 32) without a trip through LDS: the swap exchanges lanes 32-63 of its first
-// operand with lanes 0-31 of its second, leaving (low half, low half) and (high half, high half).
-__device__ __forceinline__ float max_with_other_half(float x) {
-    float lo = x, hi = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
-    return fmaxf(lo, hi);
-}
-
 // One key tile for one wave; slot = LDS byte offset of the (K tile, V^T tile) pair.
 // Issue order is pinned segment by segment (one MFMA each, scheduling barriers between): an
 // MFMA holds the matrix pipe for 32 cycles, a plain VALU op issues in 4 and exp2 in 8, so the

@@ -137,7 +137,6 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t wave_lds = smem_base + (uint32_t)wave * (kLoads * 1024);
     const uint32_t k0 = smem_base + rho(lq) * kRowB + ((hh ^ (lq & (kKChunks - 1))) << 4);
-    const int swap_addr = (lane ^ 32) << 2;
 #define VEDA_LOAD_K(j_tile, SLOT)                                                                \
     do {                                                                                         \
         const char* src_ = kt + (int64_t)(j_tile) * kKBytes;                                     \
@@ -150,7 +149,6 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         __builtin_amdgcn_s_waitcnt(0x0F70);     \
         __syncthreads();                        \
     } while (0)
-#define VEDA_SWAP32(X) __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(swap_addr, __builtin_bit_cast(int, (X))))
 
     // ---- pass 1: row maximum m (log2 units) and denominator l of the full softmax ----
     float m = -INFINITY, l = 0.0f;
@@ -167,7 +165,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
-            mx = fmaxf(mx, VEDA_SWAP32(mx));
+            mx = max_with_other_half(mx);
             const float m_new = fmaxf(m, mx);            // finite: every tile has a real slot
             float psum = 0.0f;
 #pragma unroll
@@ -179,7 +177,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         }
         VEDA_LOADS_DONE_BARRIER();
     }
-    l += VEDA_SWAP32(l);                                 // the two lane halves hold different keys
+    l = sum_with_other_half(l);                          // the two lane halves hold different keys
     const float inv_l = 1.0f / l;
 
     // ---- pass 2: block maxima of exp2(s - m) / l ----
@@ -213,7 +211,7 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
-            mx = fmaxf(mx, VEDA_SWAP32(mx));
+            mx = max_with_other_half(mx);
             const float val = q_real ? __builtin_amdgcn_exp2f(mx - m) * inv_l : 0.0f;
             blockmax = wave_max(val);
         }
@@ -223,7 +221,6 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
     publish(n - 1);
 #undef VEDA_LOAD_K
 #undef VEDA_LOADS_DONE_BARRIER
-#undef VEDA_SWAP32
 }
 
 // fp32: thread (q = tid/4, part = tid%4) holds the logits of query row q against keys part+4e.
