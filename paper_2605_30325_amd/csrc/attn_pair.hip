@@ -19,7 +19,7 @@
 // lane-half owns are contiguous in the channel-major V tile.  One step of one wave:
 //     S^T block 0 (8 MFMA) | S^T block 1 (8 MFMA; the row maximum of block 0 in its shadow)
 //     row maximum, reference check, first 8 exponentials          (matrix pipe idle: other wave)
-//     4 x [ 4 MFMA of O^T += V^T P^T ; the next 8 exponentials in their shadow ]
+//     4 x [ 4 MFMA of O^T += V^T P^T ; the next 8 exponentials in their shadow ]   (at raised wave priority)
 // K/V tiles are double buffered (2 x 32 KB at d = 128) and filled by direct global->LDS loads
 // issued one step ahead.
 #include "attn_common.h"
@@ -162,6 +162,10 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
     } while (0)
 #pragma unroll
     for (int e = 0; e < 8; e += 2) VEDA_EXP(0, e);
+    // The wave that has reached its O^T products goes first at the issue port: the other wave
+    // of the SIMD (in its own softmax section, all vector ops) otherwise delays these MFMAs and
+    // the matrix pipe idles.  Measured: 6 % fewer cycles for the whole kernel.
+    __builtin_amdgcn_s_setprio(1);
     __builtin_amdgcn_sched_barrier(0);
     // O^T += V^T P^T; the 8 exponentials of the next key step are spread over this key step's
     // NB MFMAs
@@ -177,6 +181,7 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_setprio(0);
     st.l_run += psum;
 #undef VEDA_EXP
 #undef VEDA_FRAG
