@@ -44,29 +44,46 @@ __device__ __forceinline__ float wave_max(float x) {
     return x;
 }
 
-// S^T (64 keys x 32 queries, two 32x32 blocks) of one K tile in LDS, in log2 units.
+// S^T = K Q^T (64 keys x 32 queries, two 32x32 blocks) of one K tile in LDS: raw dot products,
+// padded key slots of an edge tile set to -inf.  The MFMAs are issued at raised wave priority:
+// the other wave of the SIMD, busy with vector work, otherwise delays them.
 template <int D>
 __device__ __forceinline__ void heat_logits(f32x16 (&s)[2], const bf16x8 (&qf)[D / 16], uint32_t ka, uint64_t vm,
-                                            int hh, float scale_log2) {
+                                            int hh) {
     constexpr int G = D / 16, kRowB = D * 2;
+    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[c][i] = 0.0f;
 #pragma unroll
         for (int t = 0; t < G; ++t) {
             const bf16x8 kf = hm_lds_read16((ka ^ (uint32_t)(t << 5)) + (uint32_t)(c * 32 * kRowB));
-            s[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[c], 0, 0, 0);
+            s[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], t == 0 ? zero : s[c], 0, 0, 0);
         }
     }
-    // register i of key block c is key slot 32c + 16*(i/8) + 8*hh + (i%8); padded slots -> -inf
+    __builtin_amdgcn_s_setprio(0);
+    if (vm != ~0ull) {
+        // register i of key block c is key slot 32c + 16*(i/8) + 8*hh + (i%8).  The empty asm
+        // keeps this a real branch, taken for edge tiles only.
+        asm volatile("" ::: "memory");
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * hh);
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * hh);
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            s[c][i] = ((half >> (16 * (i >> 3) + (i & 7))) & 1u) ? s[c][i] * scale_log2 : -INFINITY;
+            for (int i = 0; i < 16; ++i)
+                if (!((half >> (16 * (i >> 3) + (i & 7))) & 1u)) s[c][i] = -INFINITY;
+        }
     }
+}
+
+// Largest raw dot product of the wave's query row over the 64 keys (both lane halves).
+__device__ __forceinline__ float heat_row_max(const f32x16 (&s)[2]) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
+    return max_with_other_half(mx);
 }
 
 // kGrouped: 128-token tiles.  The geometry in `a` is that of the 64-slot halves; the workgroup's
@@ -159,19 +176,14 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         const uint64_t vm = vmask[j];
         if (active) {
             f32x16 s[2];
-            heat_logits<D>(s, qf, k0 + (uint32_t)((j & 1) * kKBytes), vm, hh, a.scale_log2);
-            float mx = -INFINITY;
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
-            mx = max_with_other_half(mx);
-            const float m_new = fmaxf(m, mx);            // finite: every tile has a real slot
+            heat_logits<D>(s, qf, k0 + (uint32_t)((j & 1) * kKBytes), vm, hh);
+            // softmax_scale > 0: the largest logit is the largest dot product, scaled
+            const float m_new = fmaxf(m, heat_row_max(s) * a.scale_log2);   // finite: every tile has a real slot
             float psum = 0.0f;
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(s[c][i] - m_new);
+                for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(fmaf(s[c][i], a.scale_log2, -m_new));
             l = l * __builtin_amdgcn_exp2f(m - m_new) + psum;
             m = m_new;
         }
@@ -205,14 +217,8 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
         float blockmax = 0.0f;
         if (active) {
             f32x16 s[2];
-            heat_logits<D>(s, qf, k0 + (uint32_t)((j & 1) * kKBytes), vm, hh, a.scale_log2);
-            float mx = -INFINITY;
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
-            mx = max_with_other_half(mx);
-            const float val = q_real ? __builtin_amdgcn_exp2f(mx - m) * inv_l : 0.0f;
+            heat_logits<D>(s, qf, k0 + (uint32_t)((j & 1) * kKBytes), vm, hh);
+            const float val = q_real ? __builtin_amdgcn_exp2f(fmaf(heat_row_max(s), a.scale_log2, -m)) * inv_l : 0.0f;
             blockmax = wave_max(val);
         }
         if (lane == 0) part[j & 1][wave] = blockmax;
