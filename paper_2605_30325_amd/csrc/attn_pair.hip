@@ -67,7 +67,7 @@ struct PairAddr {
 // kAhead MFMAs before their consumer.
 template <int D>
 __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, uint64_t vm, uint32_t slot) {
-    constexpr int G = D / 16, NB = D / 32, kAhead = 4;
+    constexpr int G = D / 16, NB = D / 32, kAhead = 6;
     constexpr int kRowB = D * 2;
     constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
     const uint32_t ka = fa.k0 + slot, va = fa.v0 + slot;
