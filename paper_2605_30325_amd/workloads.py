@@ -144,7 +144,10 @@ def smooth_field(wl: Workload, tensor: str, head: int, device="cpu",
                + ph[None, None, None, :, m])
         out += am[None, None, None, :, m] * torch.sin(ang)
     out = out.reshape(T * H * W, d)
-    out /= out.std(dim=0, keepdim=True, unbiased=False).clamp_min(1e-12)
+    # A channel whose sinusoids do not vary over this grid (e.g. frequencies along t only and
+    # T = 1) is left as the constant it is instead of being blown up by a near-zero deviation.
+    std = out.std(dim=0, keepdim=True, unbiased=False)
+    out /= torch.where(std < 1e-6, torch.ones_like(std), std)
     return out
 
 

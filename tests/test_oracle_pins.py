@@ -5,6 +5,7 @@ from pathlib import Path
 
 import numpy as np
 import pytest
+import torch
 
 from oracle import oracle as vo
 from paper_2605_30325_amd import workloads as wlm
@@ -434,3 +435,14 @@ def test_workload_sizes_match_the_size_table():
     q = wlm.make_head(w["tiny"], "q", 0)
     assert q.shape == (256, 64) and q.dtype.is_floating_point
     assert np.array_equal(q.numpy(), wlm.make_head(w["tiny"], "q", 0).numpy())
+
+
+def test_generated_values_stay_bounded_on_degenerate_grids():
+    # With T = 1 a channel whose sinusoids only vary along t is constant over the grid; the
+    # unit-variance normalisation must leave it alone instead of dividing by ~0.
+    wl = wlm.custom_workload("flat", 4, 128, "bf16", (1, 15, 17), True, (58, 100), 357998, batch=2)
+    for b in range(2):
+        for h in range(4):
+            for t in ("q", "k", "v"):
+                x = wlm.make_head(wl, t, h, batch=b).float()
+                assert torch.isfinite(x).all() and float(x.abs().max()) < 16.0
