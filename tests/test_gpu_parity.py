@@ -496,6 +496,11 @@ def test_128_token_tiles_whole_path(d):
     shapes = np.asarray([(8, 4, 4), (2, 8, 8), (32, 2, 2), (1, 8, 16), (1, 1, 128)], np.int32)
     wl = wlm.custom_workload(f"b128_{d}", len(shapes), d, "bf16", (9, 18, 18), True, (25, 100), seed=81, batch=2,
                              latent_dim=32)
+    _whole_path_128(wl, shapes)
+
+
+def _whole_path_128(wl, shapes):
+    d = wl.head_dim
     dev = torch.device("cuda:0")
     q, k, v = wlm.make_qkv(wl, dev)
     plan = veda.Plan(wl.batch, wl.heads, d, wl.grid, shapes, wl.torch_dtype, tile_tokens=128)
@@ -516,7 +521,7 @@ def test_128_token_tiles_whole_path(d):
     assert torch.isfinite(out.float()).all()
     # target tile scores over whole 128-token tiles, all rows and then a subset
     heat = veda.veda_tile_heatmap(plan, qt, kt, vm, scale)
-    some = np.asarray(sorted({0, plan.total_tiles - 1, plan.tile_offset[2] + 1}), np.int32)
+    some = np.asarray(sorted({0, plan.total_tiles - 1, plan.tile_offset[wl.heads // 2] + 1}), np.int32)
     part = torch.full_like(heat, -7.0)
     veda.veda_tile_heatmap(plan, qt, kt, vm, scale, torch.as_tensor(some).to(dev), part)
     torch.cuda.synchronize()
