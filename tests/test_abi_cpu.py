@@ -28,6 +28,20 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_public_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, no C++ and no HIP types
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "veda.h"\nint main(void) { return (int)sizeof(veda_problem) == 0; }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", f"-I{ROOT / 'include'}",
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_status_strings(lib):
     assert lib.veda_status_string(0) == b"ok"
     assert b"workspace" in lib.veda_status_string(veda.VEDA_ERR_WORKSPACE)
