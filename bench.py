@@ -14,7 +14,9 @@ import argparse
 import json
 import math
 import os
+import re
 import sys
+import threading
 import time
 from pathlib import Path
 
@@ -87,6 +89,47 @@ def cpu_baseline(wl, shapes, kph, dense_flops, q, k, v, eq, ek, score_scale, sof
                    f"({total_s:.0f} s per call)"),
         "extrapolated_s_per_call": total_s,
     }
+
+
+class ShaderClockSampler(threading.Thread):
+    """Reads the shader clock the driver reports for device 0 (sysfs pp_dpm_sclk, the starred
+    entry) every few milliseconds while the timed steps run: the attention kernel is power-limited,
+    so the clock it is held at belongs next to its rate.  Yields nothing if the file is missing."""
+
+    def __init__(self, period_s: float = 0.003):
+        super().__init__(daemon=True)
+        self.period, self.samples, self.stop_flag, self.path = period_s, [], threading.Event(), None
+        try:
+            import glob
+            import torch
+            props = torch.cuda.get_device_properties(0)
+            want = "%04x:%02x:%02x." % (props.pci_domain_id, props.pci_bus_id, props.pci_device_id)
+            for dev in glob.glob("/sys/class/drm/card*/device"):
+                if os.path.realpath(dev).split("/")[-1].startswith(want) and os.path.exists(dev + "/pp_dpm_sclk"):
+                    self.path = dev + "/pp_dpm_sclk"
+        except Exception:
+            self.path = None
+
+    def run(self):
+        if self.path is None:
+            return
+        pat = re.compile(r"(\d+)\s*[Mm][Hh]z\s*\*")
+        while not self.stop_flag.is_set():
+            try:
+                m = pat.search(open(self.path).read())
+                if m:
+                    self.samples.append(int(m.group(1)))
+            except OSError:
+                return
+            time.sleep(self.period)
+
+    def summary(self):
+        self.stop_flag.set()
+        self.join(timeout=1.0)
+        if not self.samples:
+            return None
+        a = self.samples
+        return {"mean": sum(a) / len(a), "min": float(min(a)), "max": float(max(a)), "samples": len(a)}
 
 
 def main():
@@ -175,11 +218,14 @@ def main():
         run()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
+    clock = ShaderClockSampler()
+    clock.start()
     t0 = time.perf_counter()
     for i in range(args.steps):
         run(evs[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    sclk = clock.summary()
     ms_per_step = wall * 1e3 / args.steps
     first = 3 if args.attn_only else 0
     stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps
@@ -209,6 +255,11 @@ def main():
                      "frac": kept_tflops / (PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if B == 64 else None,
                      "flops_per_launch": kept_flops, "kv_tile_bytes_per_launch": bytes_attn_kv},
+        # clock the driver reported during the timed steps, and the rate against the matrix peak
+        # at that clock (256 CUs x 4096 FLOP per clock)
+        "sclk_mhz": sclk,
+        "mfma_util_at_observed_clock": (kept_tflops * 1e12 / (sclk["mean"] * 1e6 * 256 * 4096)
+                                        if sclk and wl.dtype == "bf16" else None),
     }
     if not args.attn_only:
         result["stage_hbm_gbps"] = {
