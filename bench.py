@@ -231,6 +231,9 @@ def main():
     stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps
                 for i, n in enumerate(names) if i >= first}
     attn_ms = stage_ms["attn"]
+    attn_each = sorted(e[3].elapsed_time(e[4]) for e in evs)
+    attn_ms_median = attn_each[len(attn_each) // 2] if len(attn_each) % 2 else 0.5 * (
+        attn_each[len(attn_each) // 2 - 1] + attn_each[len(attn_each) // 2])
     kept_tflops = kept_flops / (attn_ms * 1e-3) / 1e12
 
     result = {
@@ -243,7 +246,8 @@ def main():
         "config": {"workload": wl.name, "grid": list(wl.grid), "tokens": N, "heads": heads, "head_dim": d,
                    "tile_tokens": B, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
                    "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch)},
-        "attn_ms_per_call": attn_ms,
+        "attn_ms_per_call": attn_ms, "attn_ms_median": attn_ms_median,
+        "attn_ms_min": attn_each[0], "attn_ms_max": attn_each[-1],
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
         "attn_kept_tflops": kept_tflops,
         "stage_ms": stage_ms,
