@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--workload", default="waver12b_720p_241f")
     ap.add_argument("--keep", default=None, help="kept fraction NUM/DEN (default: the workload's)")
     ap.add_argument("--dense", action="store_true", help="also time one dense (k = N_T) attention call")
+    ap.add_argument("--two-stage", action="store_true",
+                    help="stages 2 and 3 as separate calls with the score matrix between them; default: one call "
+                         "(veda_tile_score_select*, scores never written), whose time is reported under stage "
+                         "'score' with stage 'select' 0")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
     ap.add_argument("--tile-tokens", type=int, default=64, choices=(64, 128),
@@ -177,10 +181,11 @@ def main():
         bytes_layout += stat_bytes
         bytes_score = stat_bytes + int((tiles * tiles).sum()) * 4 * wl.batch
     bytes_select = int((tiles * tiles).sum()) * 4 * wl.batch + pairs * 4
+    # one call: descriptors (or tiles) in, lists out; the score matrix makes no round trip
+    bytes_score_select = bytes_score - int((tiles * tiles).sum()) * 4 * wl.batch + pairs * 4
     bytes_attn_kv = pairs * 2 * B * d * es
 
     bufs = {}
-    names = ("layout", "score", "select", "attn")
 
     def step(events=None):
         ev = events
@@ -194,12 +199,24 @@ def main():
             bufs.update(zq=zq, zk=zk)
         vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
         if ev: ev[1].record()
-        if args.unfused:
-            s, ws = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
+        if not args.two_stage:
+            s = None
+            if args.unfused:
+                rp, ci, ws = veda.veda_tile_score_select(plan, pq, pk, score_scale, kph, q_tiled=qt, k_tiled=kt,
+                                                         valid_mask=vm, row_ptr=bufs.get("rp"),
+                                                         col_idx=bufs.get("ci"), workspace=bufs.get("ws"))
+            else:
+                rp, ci, ws = veda.veda_tile_score_select(plan, pq, pk, score_scale, kph, stats_q=zq, stats_k=zk,
+                                                         row_ptr=bufs.get("rp"), col_idx=bufs.get("ci"),
+                                                         workspace=bufs.get("ws"))
+            if ev: ev[2].record()
         else:
-            s, ws = veda.veda_tile_score_stats(plan, zq, zk, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
-        if ev: ev[2].record()
-        rp, ci = veda.veda_tile_select(plan, s, kph, bufs.get("rp"), bufs.get("ci"))
+            if args.unfused:
+                s, ws = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
+            else:
+                s, ws = veda.veda_tile_score_stats(plan, zq, zk, pq, pk, score_scale, bufs.get("s"), bufs.get("ws"))
+            if ev: ev[2].record()
+            rp, ci = veda.veda_tile_select(plan, s, kph, bufs.get("rp"), bufs.get("ci"))
         if ev: ev[3].record()
         out, _ = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
         if ev: ev[4].record()
@@ -227,9 +244,13 @@ def main():
     wall = time.perf_counter() - t0
     sclk = clock.summary()
     ms_per_step = wall * 1e3 / args.steps
-    first = 3 if args.attn_only else 0
-    stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps
-                for i, n in enumerate(names) if i >= first}
+    # event index pairs of the stages; one call for stages 2+3 leaves no event between them
+    spans = {"layout": (0, 1), "score": (1, 2), "select": (2, 3), "attn": (3, 4)}
+    if not args.two_stage:
+        spans = {"layout": (0, 1), "score_select": (1, 3), "attn": (3, 4)}
+    if args.attn_only:
+        spans = {"attn": (3, 4)}
+    stage_ms = {n: sum(e[i].elapsed_time(e[j]) for e in evs) / args.steps for n, (i, j) in spans.items()}
     attn_ms = stage_ms["attn"]
     attn_each = sorted(e[3].elapsed_time(e[4]) for e in evs)
     attn_ms_median = attn_each[len(attn_each) // 2] if len(attn_each) % 2 else 0.5 * (
@@ -266,15 +287,15 @@ def main():
                                         if sclk and wl.dtype == "bf16" else None),
     }
     if not args.attn_only:
-        result["stage_hbm_gbps"] = {
-            "layout": bytes_layout / (stage_ms["layout"] * 1e-3) / 1e9,
-            "score": bytes_score / (stage_ms["score"] * 1e-3) / 1e9,
-            "select": bytes_select / (stage_ms["select"] * 1e-3) / 1e9,
-        }
+        stage_bytes = {"layout": bytes_layout, "score": bytes_score, "select": bytes_select,
+                       "score_select": bytes_score_select}
+        result["stage_hbm_gbps"] = {n: stage_bytes[n] / (ms * 1e-3) / 1e9 for n, ms in stage_ms.items() if n != "attn"}
         result["stage_hbm_frac"] = {n: g / PEAK_HBM_GBPS for n, g in result["stage_hbm_gbps"].items()}
 
     if args.dense:
         kd = np.asarray(plan.tiles, np.int32)
+        if bufs.get("s") is None:   # k = N_T keeps every tile whatever the scores are
+            bufs["s"] = torch.zeros((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
         rp_d, ci_d = veda.veda_tile_select(plan, bufs["s"], kd)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         veda.veda_sparse_attn_fwd(plan, bufs["qt"], bufs["kt"], bufs["vt"], bufs["vm"], rp_d, ci_d, softmax_scale, bufs["out"])

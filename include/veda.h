@@ -163,6 +163,29 @@ veda_status veda_tile_score_closed_form(const veda_plan*, const void* q_tiled, c
 veda_status veda_tile_select(const veda_plan*, const float* scores, const int32_t* k_per_head,
                              int32_t* row_ptr, int32_t* col_idx, void* stream);
 
+/* ---- stages 2 + 3 in one call, the score matrix never written (Eq. 5; Sec. 3.1 "exactly k
+ * per row"; Alg. 2; the Conclusion names tighter fusion of mask preparation as the next step
+ * for the kernels) ---------------------------------------------------------------------------- */
+/* veda_tile_score_select       = veda_tile_score followed by veda_tile_select,
+ * veda_tile_score_select_stats = veda_tile_score_stats followed by veda_tile_select,
+ * with identical row_ptr / col_idx (same arithmetic, same order, same tie rule), but for heads
+ * with at least 1024 tiles, a small keep budget and out_dim <= 64 every score is compared with a
+ * per-row pivot as soon as it is formed and only the candidates of the row's top-k reach memory;
+ * a row whose candidates do not hold its top-k is redone on its full score row.  Other shapes
+ * take the two-stage route inside the call.
+ * workspace  device scratch of at least veda_plan_fused_workspace_bytes() (latents, candidate
+ *            lists, and room for the score matrix, of which only redone rows are touched);
+ *            contents undefined after. */
+size_t veda_plan_fused_workspace_bytes(const veda_plan*, const veda_mlp* phi_q, const veda_mlp* phi_k);
+veda_status veda_tile_score_select(const veda_plan*, const void* q_tiled, const void* k_tiled,
+                                   const uint64_t* valid_mask, const veda_mlp* phi_q, const veda_mlp* phi_k,
+                                   float scale, const int32_t* k_per_head, int32_t* row_ptr, int32_t* col_idx,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+veda_status veda_tile_score_select_stats(const veda_plan*, const float* stats_q, const float* stats_k,
+                                         const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
+                                         const int32_t* k_per_head, int32_t* row_ptr, int32_t* col_idx,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- stage 4: block-sparse flash attention + un-tiling (Eq. 2; Sec. 4.3; Alg. 1 "UnTile") -- */
 /* q_tiled,k_tiled  VEDA_TOKEN_MAJOR; v_tiled VEDA_CHANNEL_MAJOR; valid_mask from stage 1.
  * row_ptr/col_idx  CSR lists as written by stage 3 (any order within a row is accepted, no

@@ -1,8 +1,8 @@
 """Builds libveda.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
 Run as `python -m paper_2605_30325_amd.build`.  Each translation unit is compiled on its
-own; score.hip additionally gets -ffp-contract=off because its fp32 results decide the
-top-k set and must follow a fixed operation order.
+own; score.hip and fused.hip additionally get -ffp-contract=off because their fp32 results decide
+the top-k set and must follow a fixed operation order.
 """
 from __future__ import annotations
 
@@ -18,10 +18,10 @@ CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libveda.so"
 
-SOURCES = ["plan.hip", "layout.hip", "score.hip", "select.hip", "attn.hip", "attn_pair.hip", "heatmap.hip"]
+SOURCES = ["plan.hip", "layout.hip", "score.hip", "select.hip", "fused.hip", "attn.hip", "attn_pair.hip", "heatmap.hip"]
 COMMON = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", f"-I{ROOT / 'include'}", f"-I{CSRC}",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
-PER_FILE = {"score.hip": ["-ffp-contract=off"]}
+PER_FILE = {"score.hip": ["-ffp-contract=off"], "fused.hip": ["-ffp-contract=off"]}
 
 
 def hipcc() -> str:

@@ -8,7 +8,7 @@
 //              with 1/count rounded once on the host; max/min by plain comparisons.
 //   phi      : per output, one fmaf chain over ascending input index started from the bias.
 //   score    : per (i,j), one fmaf chain over ascending latent index from +0, then * scale.
-#include "veda_internal.h"
+#include "score_common.h"
 
 #pragma clang fp contract(off)
 
@@ -253,7 +253,8 @@ constexpr int kSPitch = 36;   // LDS pitch of one staged latent row (floats): ro
 __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
                                                     const float* __restrict__ yq, const float* __restrict__ yk,
                                                     float* __restrict__ scores, int dp, float scale,
-                                                    int64_t total_tiles, int64_t score_elems) {
+                                                    int64_t total_tiles, int64_t score_elems,
+                                                    const int32_t* __restrict__ flags) {
     __shared__ __align__(16) float qs[kSB * kSPitch];
     __shared__ __align__(16) float ks[kSB * kSPitch];
     int lo = 0, hi = n_heads - 1;   // last head whose first block is <= blockIdx.x
@@ -268,6 +269,11 @@ __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__
     const int nT = hg.n_tiles;
     const float* qbase = yq + (b * total_tiles + hg.tile_off) * dp;
     const float* kbase = yk + (b * total_tiles + hg.tile_off) * dp;
+    if (flags) {   // only the blocks of rows that asked for their full score row
+        const int r = bi * kSB + (int)threadIdx.x;
+        const int mine = (threadIdx.x < kSB && r < nT) ? flags[b * total_tiles + hg.tile_off + r] : 0;
+        if (!__syncthreads_or(mine)) return;
+    }
     const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
     float acc[8][8];
 #pragma unroll
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__
     }
 }
 
-static veda_status check_mlp(const veda_plan* pl, const veda_mlp* m) {
+veda_status check_mlp(const veda_plan* pl, const veda_mlp* m) {
     if (!m || !m->w1 || !m->b1) return VEDA_ERR_INVALID_ARG;
     if (m->in_dim != 3 * pl->prob.head_dim) return VEDA_ERR_INVALID_ARG;
     if (m->hidden < 0 || m->out_dim < 1) return VEDA_ERR_INVALID_ARG;
@@ -336,7 +342,7 @@ static void fill_recip(RecipTable& recip) {
 }
 
 // TripPool (Eq. 4) of the tiled Q and K into zq, zk.
-static void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_tiled, const uint64_t* valid_mask,
+void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_tiled, const uint64_t* valid_mask,
                             float* zq, float* zk, hipStream_t s) {
     const int d = pl->prob.head_dim;
     const int64_t total = pl->total_tiles, rows = total * pl->prob.batch;
@@ -381,13 +387,9 @@ __global__ __launch_bounds__(256) void closed_form_latent_kernel(const float* __
     y[d + c] = root_lambda * sqrtf(p);
 }
 
-// Projections (Eq. 5 phi_q, phi_k) of the descriptors zq, zk into yq, yk, then the score blocks.
-static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
-                                     const float* zq, const float* zk, float* yq, float* yk, float* scores,
-                                     hipStream_t s) {
-    const int dp = phi_q->out_dim;
-    const int64_t total = pl->total_tiles;
-    veda_status st;
+// Projections (Eq. 5 phi_q, phi_k) of the descriptors zq, zk into the latents yq, yk.
+veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, const float* zq,
+                               const float* zk, float* yq, float* yk, hipStream_t s) {
     MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
     MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
     const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
@@ -397,14 +399,26 @@ static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q,
         VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     dim3 mgrid((unsigned)pl->row_blocks, 2, (unsigned)pl->prob.batch);
     hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_row_blk, zq, zk, yq,
-                       yk, pq, pk, total);
-    st = launch_status("mlp_kernel");
-    if (st != VEDA_OK) return st;
+                       yk, pq, pk, pl->total_tiles);
+    return launch_status("mlp_kernel");
+}
 
+// The score blocks of all heads (Eq. 5) from latents of dp coordinates.  flags != nullptr: only
+// the 128-row blocks that hold a flagged row (flags is indexed like the rows of the latents).
+veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
+                                float scale, const int32_t* flags, hipStream_t s) {
     dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
     hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, dp,
-                       scale, total, pl->score_elems);
+                       scale, pl->total_tiles, pl->score_elems, flags);
     return launch_status("score_kernel");
+}
+
+static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
+                                     const float* zq, const float* zk, float* yq, float* yk, float* scores,
+                                     hipStream_t s) {
+    const veda_status st = launch_projections(pl, phi_q, phi_k, zq, zk, yq, yk, s);
+    if (st != VEDA_OK) return st;
+    return launch_score_blocks(pl, yq, yk, scores, phi_q->out_dim, scale, nullptr, s);
 }
 
 }  // namespace veda
@@ -478,8 +492,5 @@ extern "C" veda_status veda_tile_score_closed_form(const veda_plan* pl, const vo
     hipLaunchKernelGGL(closed_form_latent_kernel, lgrid, dim3(256), 0, s, zq, zk, yq, yk, rows, d, sqrtf(lambda));
     st = launch_status("closed_form_latent_kernel");
     if (st != VEDA_OK) return st;
-    dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
-    hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, 2 * d, 1.0f,
-                       pl->total_tiles, pl->score_elems);
-    return launch_status("score_kernel");
+    return launch_score_blocks(pl, yq, yk, scores, 2 * d, 1.0f, nullptr, s);
 }

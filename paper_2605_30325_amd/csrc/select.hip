@@ -7,113 +7,9 @@
 // threshold are kept, and of the keys equal to it the lowest-indexed ones fill the remainder,
 // which is exactly "ties go to the lower tile index".  Ballot prefix counts emit the kept
 // columns in ascending order.  No atomics: the output is deterministic.
-#include <cmath>
-
-#include "veda_internal.h"
+#include "select_common.h"
 
 namespace veda {
-
-struct SelectArgs {
-    int32_t k[kMaxHeads];          // kept tiles per row, per head
-    int64_t col_off[kMaxHeads];    // first col_idx element of each head (within one batch)
-    int64_t nnz_per_batch;
-};
-
-__device__ inline uint32_t score_key(float s) {
-    s = (s != s) ? -INFINITY : s + 0.0f;
-    const uint32_t u = __float_as_uint(s);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Exact selection on one row by one wavefront.  ITEMS > 0: the row (n <= 64*ITEMS columns)
-// lives in registers.  ITEMS == 0: any length, re-read from memory (L2) on every pass.
-template <int ITEMS>
-__device__ __forceinline__ void select_row(const float* __restrict__ srow, int n, int k, int32_t* __restrict__ dst,
-                                           int lane) {
-    uint32_t key[ITEMS > 0 ? ITEMS : 1];
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int t = 0; t < ITEMS; ++t) {
-            const int j = t * 64 + lane;
-            key[t] = j < n ? score_key(srow[j]) : 0u;   // 0 is below every real key
-        }
-    }
-    const int items = ITEMS > 0 ? ITEMS : (n + 63) / 64;
-    auto get = [&](int t) -> uint32_t {
-        if (ITEMS > 0) return key[t];
-        const int j = t * 64 + lane;
-        return j < n ? score_key(srow[j]) : 0u;
-    };
-
-    uint32_t thr = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = thr | (1u << bit);
-        int cnt = 0;
-        if (ITEMS > 0) {
-#pragma unroll
-            for (int t = 0; t < ITEMS; ++t) cnt += __popcll(__ballot(key[t] >= cand));
-        } else {
-            for (int t = 0; t < items; ++t) cnt += __popcll(__ballot(get(t) >= cand));
-        }
-        if (cnt >= k) thr = cand;
-    }
-    // thr is now the k-th largest key of the row.
-    int n_gt = 0;
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int t = 0; t < ITEMS; ++t) n_gt += __popcll(__ballot(key[t] > thr));
-    } else {
-        for (int t = 0; t < items; ++t) n_gt += __popcll(__ballot(get(t) > thr));
-    }
-    int ties_left = k - n_gt;   // >= 1
-    int written = 0;
-    const uint64_t below = (1ull << lane) - 1ull;
-    auto emit = [&](int t, uint32_t kv) {
-        const int j = t * 64 + lane;
-        const bool gt = kv > thr;
-        const bool eq = (kv == thr) && j < n;
-        const uint64_t eq_b = __ballot(eq);
-        const bool take = gt || (eq && __popcll(eq_b & below) < ties_left);
-        const uint64_t take_b = __ballot(take);
-        if (take) dst[written + __popcll(take_b & below)] = j;
-        written += __popcll(take_b);
-        const int eq_n = __popcll(eq_b);
-        ties_left = ties_left > eq_n ? ties_left - eq_n : 0;
-    };
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int t = 0; t < ITEMS; ++t) emit(t, key[t]);
-    } else {
-        for (int t = 0; t < items; ++t) emit(t, get(t));
-    }
-}
-
-// Everything a wavefront needs to know about its row.
-struct RowInfo {
-    const float* srow;
-    int32_t* dst;
-    int n, k, head;
-};
-
-__device__ __forceinline__ RowInfo locate_row(const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
-                                              const float* __restrict__ scores, const SelectArgs& args,
-                                              int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_idx,
-                                              int64_t total_tiles, int64_t score_elems, int64_t rows, int64_t row,
-                                              int lane) {
-    const int64_t b = row / total_tiles;
-    const int64_t g = row - b * total_tiles;
-    const int head = tile_head[g];
-    const HeadGeom hg = heads[head];
-    const int n = hg.n_tiles;
-    const int k = args.k[head];
-    const int i = (int)(g - hg.tile_off);
-    const int64_t out_off = b * args.nnz_per_batch + args.col_off[head] + (int64_t)i * k;
-    if (lane == 0) {
-        row_ptr[row] = (int32_t)out_off;
-        if (row == rows - 1) row_ptr[rows] = (int32_t)(out_off + k);
-    }
-    return RowInfo{scores + b * score_elems + hg.score_off + (int64_t)i * n, col_idx + out_off, n, k, head};
-}
 
 template <int ITEMS>
 __global__ __launch_bounds__(256) void select_kernel(const HeadGeom* __restrict__ heads,
@@ -128,59 +24,6 @@ __global__ __launch_bounds__(256) void select_kernel(const HeadGeom* __restrict_
                                   row, lane);
     select_row<ITEMS>(ri.srow, ri.n, ri.k, ri.dst, lane);
 }
-
-// Long rows with a small keep budget: a pivot from a sample shrinks the row to a short
-// candidate list before the exact search.
-//   1. 256 columns spread evenly over the row are sampled; the pivot p is the sample's m-th
-//      largest value (m per head from the host, a few standard deviations above 256*k/n, so
-//      that the row almost surely has at least k values >= p, and not many more).
-//   2. One pass over the row copies (key, column) of every value >= p to LDS, in column order.
-//   3. If between k and 1024 candidates came out, the k-th largest row value is the k-th
-//      largest candidate: the same bitwise search and tie rule run on the candidates only.
-//      Otherwise the row is handled by the plain search over the whole row.
-// The result is the exact top-k set whichever way is taken.
-constexpr int kCandCap = 1024;
-constexpr int kSample = 256;
-
-template <int NI>
-__device__ __forceinline__ void select_candidates(const uint32_t* ckey, const int32_t* ccol, int m_cand, int k,
-                                                  int32_t* __restrict__ dst, int lane) {
-    uint32_t key[NI];
-#pragma unroll
-    for (int t = 0; t < NI; ++t) {
-        const int c = t * 64 + lane;
-        key[t] = c < m_cand ? ckey[c] : 0u;
-    }
-    uint32_t thr = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = thr | (1u << bit);
-        int cnt = 0;
-#pragma unroll
-        for (int t = 0; t < NI; ++t) cnt += __popcll(__ballot(key[t] >= cand));
-        if (cnt >= k) thr = cand;
-    }
-    int n_gt = 0;
-#pragma unroll
-    for (int t = 0; t < NI; ++t) n_gt += __popcll(__ballot(key[t] > thr));
-    int ties_left = k - n_gt;
-    int written = 0;
-    const uint64_t below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int t = 0; t < NI; ++t) {
-        const int c = t * 64 + lane;
-        const bool gt = key[t] > thr;
-        const bool eq = (key[t] == thr) && c < m_cand;
-        const uint64_t eq_b = __ballot(eq);
-        const bool take = gt || (eq && __popcll(eq_b & below) < ties_left);
-        const uint64_t take_b = __ballot(take);
-        if (take) dst[written + __popcll(take_b & below)] = ccol[c];
-        written += __popcll(take_b);
-        const int eq_n = __popcll(eq_b);
-        ties_left = ties_left > eq_n ? ties_left - eq_n : 0;
-    }
-}
-
-struct SampleArgs { int32_t m[kMaxHeads]; };   // pivot rank in the sample per head; 0 = no sampling
 
 __global__ __launch_bounds__(256) void select_sampled_kernel(const HeadGeom* __restrict__ heads,
                                                              const uint8_t* __restrict__ tile_head,
@@ -247,38 +90,40 @@ __global__ __launch_bounds__(256) void select_sampled_kernel(const HeadGeom* __r
     else select_candidates<16>(cand_key[w], cand_col[w], m_cand, k, ri.dst, lane);
 }
 
-}  // namespace veda
-
-extern "C" veda_status veda_tile_select(const veda_plan* pl, const float* scores, const int32_t* k_per_head,
-                                        int32_t* row_ptr, int32_t* col_idx, void* stream) {
-    using namespace veda;
-    if (!pl || !scores || !k_per_head || !row_ptr || !col_idx) return VEDA_ERR_INVALID_ARG;
-    SelectArgs args;
+// Per-head tables of a selection call.  Returns false on a bad budget or a list too long for
+// the int32 row pointers.  sampled: every head has long rows and a keep budget small enough that
+// the expected candidate count (n*m/256, m = pivot rank) stays well inside the candidate list.
+bool select_setup(const veda_plan* pl, const int32_t* k_per_head, SelectArgs& args, SampleArgs& sample,
+                  bool& sampled, int& max_tiles) {
     int64_t off = 0;
-    int max_tiles = 0;
+    max_tiles = 0;
+    sampled = true;
     for (int h = 0; h < pl->prob.heads; ++h) {
         const int n = pl->heads[h].n_tiles;
-        if (k_per_head[h] < 1 || k_per_head[h] > n) return VEDA_ERR_INVALID_ARG;
+        if (k_per_head[h] < 1 || k_per_head[h] > n) return false;
         args.k[h] = k_per_head[h];
         args.col_off[h] = off;
         off += (int64_t)n * k_per_head[h];
         max_tiles = n > max_tiles ? n : max_tiles;
-    }
-    args.nnz_per_batch = off;
-    if (off * pl->prob.batch >= ((int64_t)1 << 31)) return VEDA_ERR_UNSUPPORTED;  // row_ptr is int32
-    const int64_t rows = pl->total_tiles * pl->prob.batch;
-    dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-    hipStream_t s = (hipStream_t)stream;
-    // Sampled selection when every head has long rows and a keep budget small enough that the
-    // expected candidate count (n*m/256, m = pivot rank) stays well inside the LDS list.
-    SampleArgs sample;
-    bool sampled = true;
-    for (int h = 0; h < pl->prob.heads; ++h) {
-        const double n = pl->heads[h].n_tiles, f = k_per_head[h] / n;
+        const double f = k_per_head[h] / (double)n;
         const int m = (int)std::ceil(kSample * f + 3.5 * std::sqrt(kSample * f * (1.0 - f)) + 1.0);
         sample.m[h] = m;
-        if (n < 1024 || m > kSample || n * m / kSample * 1.3 > kCandCap) sampled = false;
+        if (n < 1024 || m > kSample || (double)n * m / kSample * 1.3 > kCandCap) sampled = false;
     }
+    args.nnz_per_batch = off;
+    return true;
+}
+
+veda_status launch_select(const veda_plan* pl, const float* scores, const int32_t* k_per_head, int32_t* row_ptr,
+                          int32_t* col_idx, hipStream_t s) {
+    SelectArgs args;
+    SampleArgs sample;
+    bool sampled;
+    int max_tiles;
+    if (!select_setup(pl, k_per_head, args, sample, sampled, max_tiles)) return VEDA_ERR_INVALID_ARG;
+    if (args.nnz_per_batch * pl->prob.batch >= ((int64_t)1 << 31)) return VEDA_ERR_UNSUPPORTED;  // row_ptr is int32
+    const int64_t rows = pl->total_tiles * pl->prob.batch;
+    dim3 grid((unsigned)((rows + 3) / 4)), block(256);
     if (sampled) {
         hipLaunchKernelGGL(select_sampled_kernel, grid, block, 0, s, pl->d_heads, pl->d_tile_head, scores, args,
                            sample, row_ptr, col_idx, pl->total_tiles, pl->score_elems, rows);
@@ -301,4 +146,12 @@ extern "C" veda_status veda_tile_select(const veda_plan* pl, const float* scores
     }
 #undef VEDA_LAUNCH_SEL
     return launch_status("select_kernel");
+}
+
+}  // namespace veda
+
+extern "C" veda_status veda_tile_select(const veda_plan* pl, const float* scores, const int32_t* k_per_head,
+                                        int32_t* row_ptr, int32_t* col_idx, void* stream) {
+    if (!pl || !scores || !k_per_head || !row_ptr || !col_idx) return VEDA_ERR_INVALID_ARG;
+    return veda::launch_select(pl, scores, k_per_head, row_ptr, col_idx, (hipStream_t)stream);
 }

@@ -26,7 +26,8 @@ EXPORTS = (
     "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
-    "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_sparse_attn_fwd", "veda_tile_heatmap",
+    "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
+    "veda_tile_score_select", "veda_tile_score_select_stats", "veda_sparse_attn_fwd", "veda_tile_heatmap",
     "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
 
@@ -92,6 +93,14 @@ def load():
     L.veda_tile_score_closed_form.restype = C.c_int
     L.veda_tile_select.argtypes = [vp, vp, C.POINTER(i32), vp, vp, vp]
     L.veda_tile_select.restype = C.c_int
+    L.veda_plan_fused_workspace_bytes.argtypes = [vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp)]
+    L.veda_plan_fused_workspace_bytes.restype = C.c_size_t
+    L.veda_tile_score_select.argtypes = [vp, vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
+                                         C.POINTER(i32), vp, vp, vp, C.c_size_t, vp]
+    L.veda_tile_score_select.restype = C.c_int
+    L.veda_tile_score_select_stats.argtypes = [vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
+                                               C.POINTER(i32), vp, vp, vp, C.c_size_t, vp]
+    L.veda_tile_score_select_stats.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
     L.veda_sparse_attn_fwd.restype = C.c_int
     L.veda_tile_heatmap.argtypes = [vp, vp, vp, vp, C.c_float, vp, i64, vp, vp]
@@ -297,6 +306,39 @@ def veda_tile_select(plan: Plan, scores, k_per_head: Sequence[int], row_ptr: Opt
     return row_ptr, col_idx
 
 
+def veda_tile_score_select(plan: Plan, phi_q: Mlp, phi_k: Mlp, scale: float, k_per_head: Sequence[int],
+                           q_tiled=None, k_tiled=None, valid_mask=None, stats_q=None, stats_k=None,
+                           row_ptr: Optional[torch.Tensor] = None, col_idx: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None):
+    """Stages 2 + 3 in one call, from the tiled Q, K (q_tiled, k_tiled, valid_mask) or from their
+    descriptors (stats_q, stats_k).  Returns (row_ptr, col_idx, workspace)."""
+    k = np.ascontiguousarray(k_per_head, np.int32)
+    if k.size != plan.heads:
+        raise VedaError(VEDA_ERR_INVALID_ARG, "veda_tile_score_select", "k_per_head must have one entry per head")
+    from_stats = stats_q is not None
+    dev = (stats_q if from_stats else q_tiled).device
+    nnz = int(sum(int(n) * int(kk) for n, kk in zip(plan.tiles, k)))
+    if row_ptr is None:
+        row_ptr = torch.empty(plan.batch * plan.total_tiles + 1, dtype=torch.int32, device=dev)
+    if col_idx is None:
+        col_idx = torch.empty(max(1, plan.batch * max(nnz, 0)), dtype=torch.int32, device=dev)
+    sq, sk = phi_q.struct(), phi_k.struct()
+    if workspace is None:
+        need = int(load().veda_plan_fused_workspace_bytes(plan.handle, C.byref(sq), C.byref(sk)))
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    kp = k.ctypes.data_as(C.POINTER(C.c_int32))
+    nbytes = workspace.numel() * workspace.element_size()
+    if from_stats:
+        _check(load().veda_tile_score_select_stats(plan.handle, _ptr(stats_q), _ptr(stats_k), C.byref(sq), C.byref(sk),
+                                                   C.c_float(scale), kp, _ptr(row_ptr), _ptr(col_idx), _ptr(workspace),
+                                                   nbytes, _stream()), "veda_tile_score_select_stats")
+    else:
+        _check(load().veda_tile_score_select(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(valid_mask), C.byref(sq),
+                                             C.byref(sk), C.c_float(scale), kp, _ptr(row_ptr), _ptr(col_idx),
+                                             _ptr(workspace), nbytes, _stream()), "veda_tile_score_select")
+    return row_ptr, col_idx, workspace
+
+
 def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_ptr, col_idx,
                          softmax_scale: float, out: Optional[torch.Tensor] = None,
                          lse: Optional[torch.Tensor] = None, want_lse: bool = False):
@@ -358,10 +400,12 @@ def veda_output_sqerr(plan: Plan, a: torch.Tensor, b: torch.Tensor, err: Optiona
 
 
 def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,
-                   softmax_scale: float, buffers: Optional[dict] = None, fused: bool = False):
+                   softmax_scale: float, buffers: Optional[dict] = None, fused: bool = False,
+                   one_call: bool = False):
     """The whole path in call order: layout x3 -> score -> select -> sparse attention.
     fused=True takes the descriptors during the Q and K gathers (veda_tile_layout_stats +
-    veda_tile_score_stats); the results are bit-identical either way.
+    veda_tile_score_stats); one_call=True runs stages 2 and 3 through veda_tile_score_select*,
+    which never writes the score matrix; the results are bit-identical whichever way.
     `buffers` (optional dict) is filled on the first call and reused afterwards so that a
     steady-state step allocates nothing."""
     bufs = {} if buffers is None else buffers
@@ -373,11 +417,21 @@ def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, scor
         qt, vm, vc = veda_tile_layout(plan, q, VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
         kt, _, _ = veda_tile_layout(plan, k, VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
     vt, _, _ = veda_tile_layout(plan, v, VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
-    if fused:
-        s, ws = veda_tile_score_stats(plan, zq, zk, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+    if one_call:
+        s = None
+        if fused:
+            rp, ci, ws = veda_tile_score_select(plan, phi_q, phi_k, score_scale, k_per_head, stats_q=zq, stats_k=zk,
+                                                row_ptr=bufs.get("rp"), col_idx=bufs.get("ci"), workspace=bufs.get("ws"))
+        else:
+            rp, ci, ws = veda_tile_score_select(plan, phi_q, phi_k, score_scale, k_per_head, q_tiled=qt, k_tiled=kt,
+                                                valid_mask=vm, row_ptr=bufs.get("rp"), col_idx=bufs.get("ci"),
+                                                workspace=bufs.get("ws"))
     else:
-        s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
-    rp, ci = veda_tile_select(plan, s, k_per_head, bufs.get("rp"), bufs.get("ci"))
+        if fused:
+            s, ws = veda_tile_score_stats(plan, zq, zk, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+        else:
+            s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
+        rp, ci = veda_tile_select(plan, s, k_per_head, bufs.get("rp"), bufs.get("ci"))
     out, _ = veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
     bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)
     return out, bufs

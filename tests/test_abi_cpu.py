@@ -85,6 +85,11 @@ def test_stage_calls_reject_null_plan(lib):
     assert lib.veda_tile_layout_stats(None, None, s, None, None, None, None, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_score_stats(None, None, None, None, None, 0.125, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_score_closed_form(None, None, None, None, 0.5, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_score_select(None, None, None, None, None, None, 0.125, None, None, None, None, 0,
+                                      None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_tile_score_select_stats(None, None, None, None, None, 0.125, None, None, None, None, 0,
+                                            None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_plan_fused_workspace_bytes(None, None, None) == 0
     assert lib.veda_tile_heatmap(None, None, None, None, 0.125, None, 0, None, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_recall(None, None, None, None, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_output_sqerr(None, None, s, None, s, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG

@@ -312,6 +312,144 @@ def test_select_sampled_pivot_paths():
             assert np.array_equal(got[r], ref[r]), (k, r)
 
 
+def _lists_of(plan, stats_q, stats_k, pq, pk, sscale, kph):
+    """(row_ptr, col_idx) by the two-stage route and by the one-call route, from descriptors."""
+    s, _ = veda.veda_tile_score_stats(plan, stats_q, stats_k, pq, pk, sscale)
+    rp, ci = veda.veda_tile_select(plan, s, kph)
+    rp2, ci2, _ = veda.veda_tile_score_select(plan, pq, pk, sscale, kph, stats_q=stats_q, stats_k=stats_k)
+    torch.cuda.synchronize()
+    return (rp, ci), (rp2, ci2)
+
+
+def test_score_select_in_one_call_long_rows():
+    # rows of 1260 - 1840 tiles at a 5 % budget: every score is compared with its row's pivot as it
+    # is formed and never written.  Lists must equal the two-stage route's (which the other tests
+    # hold against the oracle), from tiles and from descriptors; one head is checked against the
+    # oracle directly as well.
+    wl = wlm.custom_workload("one_call", 3, 128, "bf16", (21, 45, 80), True, (5, 100), seed=3)
+    run = hz.run_gpu_path(wl)
+    dev = torch.device("cuda:0")
+    plan, kph = run.plan, run.k_per_head
+    assert min(plan.tiles) >= 1024
+    pq = veda.Mlp(run.phi_q.w1, run.phi_q.b1, run.phi_q.w2, run.phi_q.b2, run.phi_q.relu, dev)
+    pk = veda.Mlp(run.phi_k.w1, run.phi_k.b1, run.phi_k.w2, run.phi_k.b2, run.phi_k.relu, dev)
+    rp, ci, _ = veda.veda_tile_score_select(plan, pq, pk, run.score_scale, kph, q_tiled=run.bufs["qt"],
+                                            k_tiled=run.bufs["kt"], valid_mask=run.bufs["vm"])
+    torch.cuda.synchronize()
+    assert torch.equal(rp, run.bufs["rp"]) and torch.equal(ci, run.bufs["ci"])
+    _, _, _, zq = veda.veda_tile_layout_stats(plan, run.q)
+    _, _, _, zk = veda.veda_tile_layout_stats(plan, run.k, want_mask=False)
+    two, one = _lists_of(plan, zq, zk, pq, pk, run.score_scale, kph)
+    assert torch.equal(two[0], run.bufs["rp"]) and torch.equal(two[1], run.bufs["ci"])
+    assert torch.equal(one[0], run.bufs["rp"]) and torch.equal(one[1], run.bufs["ci"])
+    st = hz.check_head(run, 0, attn_tiles=4)
+    _say(f"[parity] {wl.name} head 0: lists equal on both routes and to the oracle; attention {st}")
+
+
+def test_score_select_in_one_call_ties_nan_and_redone_rows():
+    # Descriptors doctored against the candidate lists.  Head 0: every key tile is a copy of tile B
+    # except 30 of the sampled columns, which are copies of tile A.  For a row that scores A above B
+    # the pivot is A's score and only 30 < k candidates exist; for the other rows the pivot is B's
+    # score and all 1152 > 1024 tiles pass: every row of the head is redone on its full score row,
+    # all of it ties.  Head 1: key tiles are copies of six prototypes (whole runs of equal scores
+    # around the k-th place, inside the candidate lists) and 40 of them hold NaN (rank as -inf).
+    # Lists must equal the two-stage route's.
+    wl = wlm.custom_workload("one_call_ties", 2, 64, "bf16", (16, 64, 72), False, (5, 100), seed=4, latent_dim=32)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    n = plan.tiles[0]
+    assert n == 1152 and plan.tiles[1] == n
+    kph = wlm.keep_budget(wl, None, shapes)
+    assert int(kph[0]) == 58
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+    pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+    _, _, _, zq = veda.veda_tile_layout_stats(plan, q)
+    _, _, _, zk = veda.veda_tile_layout_stats(plan, k, want_mask=False)
+    tile_a, tile_b = zk[0, 7].clone(), zk[0, 500].clone()
+    zk[0, :n] = tile_b
+    sampled = torch.as_tensor([(s * n) // 256 for s in range(30)], device=dev)
+    zk[0, sampled] = tile_a
+    g = torch.Generator(device="cpu").manual_seed(5)
+    proto = torch.randint(0, 6, (n,), generator=g).to(dev)
+    zk[0, n:2 * n] = zk[0, n:n + 6][proto]
+    nan_at = torch.randperm(n, generator=g)[:40].to(dev) + n
+    zk[0, nan_at, 0] = float("nan")
+    sscale = hz.score_scale_of(wl)
+    two, one = _lists_of(plan, zq, zk, pq, pk, sscale, kph)
+    assert torch.equal(one[0], two[0]) and torch.equal(one[1], two[1])
+    # the two-stage lists themselves against the oracle's selection on the same scores
+    s, _ = veda.veda_tile_score_stats(plan, zq, zk, pq, pk, sscale)
+    ksel = int(kph[0])
+    for h in (0, 1):
+        rows = s[0, h * n * n:(h + 1) * n * n].view(n, n)[[0, 1, n // 2, n - 1]].cpu().numpy()
+        want = vo.select(rows, ksel)
+        got = two[1][h * n * ksel:(h + 1) * n * ksel].view(n, ksel)[[0, 1, n // 2, n - 1]].cpu().numpy()
+        assert np.array_equal(got, want), h
+    a_first = (s[0, :n * n].view(n, n)[:, sampled[0]] > s[0, :n * n].view(n, n)[:, 1]).sum().item()
+    _say(f"[parity] {wl.name}: head 0 redone in full ({a_first} rows short of candidates, {n - a_first} with too many)")
+
+
+def test_score_select_in_one_call_other_shapes():
+    # short rows, a large budget, 128-token tiles and a long latent: the call takes the two-stage
+    # route inside and must give the same lists
+    for tile_tokens, dp, keep in ((64, 64, (25, 100)), (128, 32, (25, 100)), (64, 128, (50, 100))):
+        if tile_tokens == 64:
+            wl = wlm.custom_workload("one_call_small", 3, 64, "bf16", (9, 18, 18), True, keep, seed=6, latent_dim=dp)
+            shapes = wlm.tile_shapes(wl)
+        else:
+            shapes = np.asarray([(8, 4, 4), (2, 8, 8), (1, 8, 16)], np.int32)
+            wl = wlm.custom_workload("one_call_128", 3, 64, "bf16", (9, 18, 18), True, keep, seed=6, latent_dim=dp)
+        dev = torch.device("cuda:0")
+        q, k, _ = wlm.make_qkv(wl, dev)
+        plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=tile_tokens)
+        kph = np.asarray([max(1, -(-n * keep[0] // keep[1])) for n in plan.tiles], np.int32)
+        eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+        pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+        pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+        qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+        kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+        sscale = hz.score_scale_of(wl)
+        s, _ = veda.veda_tile_score(plan, qt, kt, vm, pq, pk, sscale)
+        rp, ci = veda.veda_tile_select(plan, s, kph)
+        rp2, ci2, ws = veda.veda_tile_score_select(plan, pq, pk, sscale, kph, q_tiled=qt, k_tiled=kt, valid_mask=vm)
+        torch.cuda.synchronize()
+        assert torch.equal(rp, rp2) and torch.equal(ci, ci2), (tile_tokens, dp)
+        with pytest.raises(veda.VedaError) as e:
+            veda.veda_tile_score_select(plan, pq, pk, sscale, kph, q_tiled=qt, k_tiled=kt, valid_mask=vm,
+                                        workspace=ws[: ws.numel() // 2])
+        assert e.value.status == veda.VEDA_ERR_WORKSPACE
+
+
+def test_whole_path_wrapper_routes_agree():
+    # veda_attention in its four routes (descriptors from the gather or not, stages 2+3 in one call
+    # or two): same lists, same output bits; buffers of a first call are reused by a second
+    wl = wlm.custom_workload("routes", 3, 128, "bf16", (9, 18, 18), True, (25, 100), seed=12)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, v = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    kph = wlm.keep_budget(wl, None, shapes)
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+    pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+    outs = []
+    for fused in (False, True):
+        for one_call in (False, True):
+            out, bufs = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
+                                            fused=fused, one_call=one_call)
+            first = out.clone()
+            out2, _ = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
+                                          buffers=bufs, fused=fused, one_call=one_call)
+            torch.cuda.synchronize()
+            assert out2.data_ptr() == out.data_ptr() and torch.equal(out2.view(torch.int16), first.view(torch.int16))
+            outs.append((out2.view(torch.int16).clone(), bufs["ci"].clone()))
+    for o, ci in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(ci, outs[0][1])
+
+
 def test_gpu_argument_errors_launch_nothing():
     wl = wlm.WORKLOADS["tiny"]
     run = hz.run_gpu_path(wl, want_lse=False)
