@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
                                                           const int32_t* __restrict__ row_blk,
                                                           const float* __restrict__ yq, const float* __restrict__ yk,
                                                           int dp, float scale, int64_t total_tiles, SampleArgs sample,
-                                                          float* __restrict__ pivot) {
+                                                          float* __restrict__ pivot, int32_t* __restrict__ group_flags) {
     // first the operand stages of the two sample blocks, then the 64 x 256 sample scores
     __shared__ __align__(16) float smem[kFR * kSample];
     float* qs = smem;
@@ -108,6 +108,8 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
     const int64_t row_base = (int64_t)blockIdx.y * total_tiles + hg.tile_off;
     const float* qbase = yq + row_base * dp;
     const float* kbase = yk + row_base * dp;
+    // this call's "some row of these 128 asked for its full score row" marks start cleared
+    if (threadIdx.x < 2) group_flags[(row_base + r0 + 63 * threadIdx.x) >> 7] = 0;
     load_rows<4>(qs, qbase, r0, nT, dp);
     float acc[2][4][8];
 #pragma unroll
@@ -153,8 +155,7 @@ __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* _
                                                                const float* __restrict__ yq,
                                                                const float* __restrict__ yk, int dp, float scale,
                                                                int64_t total_tiles, const float* __restrict__ pivot,
-                                                               uint32_t* __restrict__ cand_key,
-                                                               int32_t* __restrict__ cand_col,
+                                                               uint2* __restrict__ cand,
                                                                int32_t* __restrict__ cand_cnt) {
     constexpr int RA = kFRA;
     __shared__ __align__(16) float qs[16 * RA * kFQPitch];
@@ -181,12 +182,15 @@ __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* _
     for (int a = 0; a < RA; ++a) {
         const int r = r0 + ti + 16 * a;
         real[a] = r < nT;
-        pv[a] = real[a] ? pivot[row_base + r] : INFINITY;   // a NaN pivot passes nothing
+        // rows past the head: their latents are zero, so are their scores, and +inf passes none of
+        // them; a NaN pivot passes nothing either
+        pv[a] = real[a] ? pivot[row_base + r] : INFINITY;
         base[a] = 0;
     }
     for (int c0 = c_begin; c0 < c_end; c0 += kFC) {
         float acc[RA][8];
         score_block<RA>(acc, qs, ks, kbase, dp, [&](int r) { return c0 + r < nT ? c0 + r : -1; });
+        const bool full = c0 + kFC <= nT;
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
             const int64_t out = (row_base + r0 + ti + 16 * a) * kCandCap + seg * kFSegCap;
@@ -194,12 +198,11 @@ __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* _
             for (int e = 0; e < 8; ++e) {
                 const float s = acc[a][e] * scale;
                 const int col = c0 + tj + 16 * e;
-                const bool pass = real[a] && col < nT && s >= pv[a];
+                const bool pass = s >= pv[a] && (full || col < nT);
                 const uint32_t mine = (uint32_t)(__ballot(pass) >> shift) & 0xffffu;
                 const int pos = base[a] + __popc(mine & below);
                 if (pass && pos < kFSegCap) {
-                    cand_key[out + pos] = score_key(s);
-                    cand_col[out + pos] = col;
+                    cand[out + pos] = make_uint2(score_key(s), (uint32_t)col);   // one 8-byte store
                 }
                 base[a] += __popc(mine);
             }
@@ -216,11 +219,11 @@ __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* _
 __global__ __launch_bounds__(256) void fused_finish_kernel(const HeadGeom* __restrict__ heads,
                                                            const uint8_t* __restrict__ tile_head,
                                                            const float* __restrict__ scratch, SelectArgs args,
-                                                           const uint32_t* __restrict__ cand_key,
-                                                           const int32_t* __restrict__ cand_col,
+                                                           const uint2* __restrict__ cand,
                                                            const int32_t* __restrict__ cand_cnt,
                                                            int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_idx,
-                                                           int32_t* __restrict__ flags, int64_t total_tiles,
+                                                           int32_t* __restrict__ flags,
+                                                           int32_t* __restrict__ group_flags, int64_t total_tiles,
                                                            int64_t score_elems, int64_t rows) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -238,21 +241,27 @@ __global__ __launch_bounds__(256) void fused_finish_kernel(const HeadGeom* __res
         seg_end[g] = m_cand;
     }
     ok = ok && m_cand >= ri.k;
-    if (lane == 0) flags[row] = ok ? 0 : 1;
+    if (lane == 0) {
+        flags[row] = ok ? 0 : 1;
+        if (!ok) group_flags[row >> 7] = 1;
+    }
     if (!ok) return;
-    const uint32_t* ckey = cand_key + row * kCandCap;
-    const int32_t* ccol = cand_col + row * kCandCap;
-    auto at = [&](int c) {   // slot of the c-th candidate of the row
+    // (key, column) pairs: keys at even words, columns at odd words of the row's slots
+    const uint32_t* ckey = reinterpret_cast<const uint32_t*>(cand + row * kCandCap);
+    const int32_t* ccol = reinterpret_cast<const int32_t*>(cand + row * kCandCap) + 1;
+    auto at = [&](int c) {   // word offset of the c-th candidate of the row
         int slot = c;
 #pragma unroll
         for (int g = 1; g < kFSeg; ++g)
             if (c >= seg_end[g - 1]) slot = g * kFSegCap + (c - seg_end[g - 1]);
-        return slot;
+        return 2 * slot;
     };
     if (m_cand <= 256) select_candidates<4>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
     else if (m_cand <= 512) select_candidates<8>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
     else select_candidates<16>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
 }
+
+constexpr int kFallbackRows = 16;
 
 // Step 4b: flagged rows, searched in full on the score rows step 4a wrote to the scratch matrix.
 __global__ __launch_bounds__(256) void fused_fallback_kernel(const HeadGeom* __restrict__ heads,
@@ -262,20 +271,24 @@ __global__ __launch_bounds__(256) void fused_fallback_kernel(const HeadGeom* __r
                                                              int32_t* __restrict__ col_idx,
                                                              const int32_t* __restrict__ flags, int64_t total_tiles,
                                                              int64_t score_elems, int64_t rows) {
+    // one wavefront looks after kFallbackRows rows: a launch of a few workgroups that costs next to
+    // nothing when no flag is up, which is the usual case
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows || !flags[row]) return;
-    const RowInfo ri = locate_row(heads, tile_head, scratch, args, row_ptr, col_idx, total_tiles, score_elems, rows,
-                                  row, lane);
-    // a lone wavefront: keep its row in registers when it fits, instead of re-reading it on every pass
-    if (ri.n <= 64 * 64) select_row<64>(ri.srow, ri.n, ri.k, ri.dst, lane);
-    else select_row<0>(ri.srow, ri.n, ri.k, ri.dst, lane);
+    const int64_t first = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * kFallbackRows;
+    for (int64_t row = first; row < first + kFallbackRows && row < rows; ++row) {
+        if (!flags[row]) continue;
+        const RowInfo ri = locate_row(heads, tile_head, scratch, args, row_ptr, col_idx, total_tiles, score_elems,
+                                      rows, row, lane);
+        // keep the row in registers when it fits, instead of re-reading it on every pass
+        if (ri.n <= 64 * 64) select_row<64>(ri.srow, ri.n, ri.k, ri.dst, lane);
+        else select_row<0>(ri.srow, ri.n, ri.k, ri.dst, lane);
+    }
 }
 
 struct FusedSpace {
     float *zq, *zk, *yq, *yk, *pivot, *scratch;
-    int32_t *cnt, *flags, *ccol;
-    uint32_t* ckey;
+    int32_t *cnt, *flags, *group_flags;
+    uint2* cand;
     size_t bytes;
 };
 
@@ -298,8 +311,8 @@ static FusedSpace carve(const veda_plan* pl, int dp, bool with_stats, void* work
     f.pivot = (float*)take(rows * sizeof(float));
     f.cnt = (int32_t*)take(rows * kFSeg * sizeof(int32_t));
     f.flags = (int32_t*)take(rows * sizeof(int32_t));
-    f.ckey = (uint32_t*)take(rows * kCandCap * sizeof(uint32_t));
-    f.ccol = (int32_t*)take(rows * kCandCap * sizeof(int32_t));
+    f.group_flags = (int32_t*)take((rows / 128 + 2) * sizeof(int32_t));
+    f.cand = (uint2*)take(rows * kCandCap * sizeof(uint2));
     f.scratch = (float*)take((size_t)pl->score_elems * (size_t)pl->prob.batch * sizeof(float));
     f.bytes = off;
     return f;
@@ -327,17 +340,18 @@ static veda_status score_select(const veda_plan* pl, const veda_mlp* phi_q, cons
     dim3 bgrid((unsigned)pl->row_blocks, (unsigned)pl->prob.batch), rgrid((unsigned)((rows + 3) / 4)), block(256);
     dim3 cgrid((unsigned)pl->row_blocks, (unsigned)(pl->prob.batch * kFSeg));
     hipLaunchKernelGGL(fused_pivot_kernel, bgrid, block, 0, s, pl->d_heads, pl->d_row_blk, f.yq, f.yk, dp, scale,
-                       pl->total_tiles, sample, f.pivot);
+                       pl->total_tiles, sample, f.pivot, f.group_flags);
     if ((st = launch_status("fused_pivot_kernel")) != VEDA_OK) return st;
     hipLaunchKernelGGL(fused_candidates_kernel, cgrid, block, 0, s, pl->d_heads, pl->d_row_blk, f.yq, f.yk, dp, scale,
-                       pl->total_tiles, f.pivot, f.ckey, f.ccol, f.cnt);
+                       pl->total_tiles, f.pivot, f.cand, f.cnt);
     if ((st = launch_status("fused_candidates_kernel")) != VEDA_OK) return st;
-    hipLaunchKernelGGL(fused_finish_kernel, rgrid, block, 0, s, pl->d_heads, pl->d_tile_head, f.scratch, args, f.ckey,
-                       f.ccol, f.cnt, row_ptr, col_idx, f.flags, pl->total_tiles, pl->score_elems, rows);
+    hipLaunchKernelGGL(fused_finish_kernel, rgrid, block, 0, s, pl->d_heads, pl->d_tile_head, f.scratch, args, f.cand,
+                       f.cnt, row_ptr, col_idx, f.flags, f.group_flags, pl->total_tiles, pl->score_elems, rows);
     if ((st = launch_status("fused_finish_kernel")) != VEDA_OK) return st;
-    st = launch_score_blocks(pl, f.yq, f.yk, f.scratch, dp, scale, f.flags, s);
+    st = launch_score_blocks(pl, f.yq, f.yk, f.scratch, dp, scale, f.group_flags, s);
     if (st != VEDA_OK) return st;
-    hipLaunchKernelGGL(fused_fallback_kernel, rgrid, block, 0, s, pl->d_heads, pl->d_tile_head, f.scratch, args,
+    dim3 fgrid((unsigned)((rows + 4 * kFallbackRows - 1) / (4 * kFallbackRows)));
+    hipLaunchKernelGGL(fused_fallback_kernel, fgrid, block, 0, s, pl->d_heads, pl->d_tile_head, f.scratch, args,
                        row_ptr, col_idx, f.flags, pl->total_tiles, pl->score_elems, rows);
     return launch_status("fused_fallback_kernel");
 }

@@ -247,33 +247,16 @@ constexpr int kSC = 32;       // latent coordinates staged per step
 constexpr int kSPitch = 36;   // LDS pitch of one staged latent row (floats): rows stay 16-byte
                               // aligned and 8 consecutive rows start in 8 different bank groups
 
-// One workgroup computes a 128x128 block of one head's score matrix (Eq. 5); thread (ti,tj)
+// A 128x128 block (bi, bj) of one head's score matrix (Eq. 5) by one workgroup; thread (ti,tj)
 // keeps the 8x8 patch rows ti+16a, columns tj+16e.  Latent rows are staged row-major in LDS,
-// 64 coordinates at a time; every score is one fmaf chain over ascending coordinate from +0.
-__global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
-                                                    const float* __restrict__ yq, const float* __restrict__ yk,
-                                                    float* __restrict__ scores, int dp, float scale,
-                                                    int64_t total_tiles, int64_t score_elems,
-                                                    const int32_t* __restrict__ flags) {
-    __shared__ __align__(16) float qs[kSB * kSPitch];
-    __shared__ __align__(16) float ks[kSB * kSPitch];
-    int lo = 0, hi = n_heads - 1;   // last head whose first block is <= blockIdx.x
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if ((int)blockIdx.x >= heads[mid].score_blk_off) lo = mid; else hi = mid - 1;
-    }
-    const HeadGeom hg = heads[lo];
-    const int blk = blockIdx.x - hg.score_blk_off;
-    const int bi = blk / hg.score_blk_dim, bj = blk - bi * hg.score_blk_dim;
-    const int64_t b = blockIdx.y;
+// 32 coordinates at a time; every score is one fmaf chain over ascending coordinate from +0.
+__device__ __forceinline__ void score_block_128(const HeadGeom& hg, int bi, int bj, int64_t b, float* qs, float* ks,
+                                                const float* __restrict__ yq, const float* __restrict__ yk,
+                                                float* __restrict__ scores, int dp, float scale,
+                                                int64_t total_tiles, int64_t score_elems) {
     const int nT = hg.n_tiles;
     const float* qbase = yq + (b * total_tiles + hg.tile_off) * dp;
     const float* kbase = yk + (b * total_tiles + hg.tile_off) * dp;
-    if (flags) {   // only the blocks of rows that asked for their full score row
-        const int r = bi * kSB + (int)threadIdx.x;
-        const int mine = (threadIdx.x < kSB && r < nT) ? flags[b * total_tiles + hg.tile_off + r] : 0;
-        if (!__syncthreads_or(mine)) return;
-    }
     const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
     float acc[8][8];
 #pragma unroll
@@ -324,6 +307,49 @@ __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__
             if (j < nT) sbase[(int64_t)i * nT + j] = acc[a][e] * scale;
         }
     }
+}
+
+// All score blocks, one workgroup each.
+__global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
+                                                    const float* __restrict__ yq, const float* __restrict__ yk,
+                                                    float* __restrict__ scores, int dp, float scale,
+                                                    int64_t total_tiles, int64_t score_elems) {
+    __shared__ __align__(16) float qs[kSB * kSPitch];
+    __shared__ __align__(16) float ks[kSB * kSPitch];
+    int lo = 0, hi = n_heads - 1;   // last head whose first block is <= blockIdx.x
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int)blockIdx.x >= heads[mid].score_blk_off) lo = mid; else hi = mid - 1;
+    }
+    const HeadGeom hg = heads[lo];
+    const int blk = blockIdx.x - hg.score_blk_off;
+    const int bi = blk / hg.score_blk_dim, bj = blk - bi * hg.score_blk_dim;
+    score_block_128(hg, bi, bj, blockIdx.y, qs, ks, yq, yk, scores, dp, scale, total_tiles, score_elems);
+}
+
+// Only the score rows somebody asked for: one workgroup per 128 rows of a head (the even
+// entries of the 64-row table), which leaves at once unless one of the marks of its rows is set
+// (marks: one per 128 consecutive rows of the latents, row >> 7) and otherwise forms all the
+// blocks of its rows.
+__global__ __launch_bounds__(256) void score_marked_rows_kernel(const HeadGeom* __restrict__ heads,
+                                                                const int32_t* __restrict__ row_blk,
+                                                                const float* __restrict__ yq,
+                                                                const float* __restrict__ yk,
+                                                                float* __restrict__ scores, int dp, float scale,
+                                                                int64_t total_tiles, int64_t score_elems,
+                                                                const int32_t* __restrict__ marks) {
+    __shared__ __align__(16) float qs[kSB * kSPitch];
+    __shared__ __align__(16) float ks[kSB * kSPitch];
+    const int32_t code = row_blk[blockIdx.x];
+    if (code & 1) return;
+    const HeadGeom hg = heads[code >> 24];
+    const int bi = (code & 0xffffff) >> 1, nT = hg.n_tiles;
+    const int64_t b = blockIdx.y;
+    const int64_t g0 = b * total_tiles + hg.tile_off + (int64_t)bi * kSB;
+    const int last = nT - 1 - bi * kSB < kSB - 1 ? nT - 1 - bi * kSB : kSB - 1;
+    if (!(marks[g0 >> 7] | marks[(g0 + last) >> 7])) return;
+    for (int bj = 0; bj < hg.score_blk_dim; ++bj)
+        score_block_128(hg, bi, bj, b, qs, ks, yq, yk, scores, dp, scale, total_tiles, score_elems);
 }
 
 veda_status check_mlp(const veda_plan* pl, const veda_mlp* m) {
@@ -403,13 +429,20 @@ veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const
     return launch_status("mlp_kernel");
 }
 
-// The score blocks of all heads (Eq. 5) from latents of dp coordinates.  flags != nullptr: only
-// the 128-row blocks that hold a flagged row (flags is indexed like the rows of the latents).
+// The score blocks of all heads (Eq. 5) from latents of dp coordinates.  marks != nullptr: one
+// mark per 128 consecutive rows of the latents (row >> 7); only the score rows of 128-row blocks
+// that touch a marked group are formed.
 veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
-                                float scale, const int32_t* flags, hipStream_t s) {
+                                float scale, const int32_t* marks, hipStream_t s) {
+    if (marks) {
+        dim3 rgrid((unsigned)pl->row_blocks, (unsigned)pl->prob.batch);
+        hipLaunchKernelGGL(score_marked_rows_kernel, rgrid, dim3(256), 0, s, pl->d_heads, pl->d_row_blk, yq, yk, scores,
+                           dp, scale, pl->total_tiles, pl->score_elems, marks);
+        return launch_status("score_marked_rows_kernel");
+    }
     dim3 sgrid((unsigned)pl->score_blocks, (unsigned)pl->prob.batch);
     hipLaunchKernelGGL(score_kernel, sgrid, dim3(256), 0, s, pl->d_heads, pl->prob.heads, yq, yk, scores, dp,
-                       scale, pl->total_tiles, pl->score_elems, flags);
+                       scale, pl->total_tiles, pl->score_elems);
     return launch_status("score_kernel");
 }
 

@@ -19,9 +19,10 @@ void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_til
 veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, const float* zq,
                                const float* zk, float* yq, float* yk, hipStream_t s);
 
-// The score blocks of all heads (Eq. 5) from latents of dp coordinates.  flags != nullptr: only
-// the 128-row blocks that hold a flagged row (flags is indexed like the rows of the latents).
+// The score blocks of all heads (Eq. 5) from latents of dp coordinates.  marks != nullptr: one
+// mark per 128 consecutive rows of the latents (row >> 7); only the score rows of 128-row blocks
+// that touch a marked group are formed.
 veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
-                                float scale, const int32_t* flags, hipStream_t s);
+                                float scale, const int32_t* marks, hipStream_t s);
 
 }  // namespace veda
