@@ -19,6 +19,8 @@
 //      and searched in full by the stage-3 search.  The result is the exact top-k either way.
 // Heads with short rows or large keep budgets (where stage 3 would not sample either) and
 // latents longer than 64 coordinates take the two-stage route through the scratch matrix.
+#include <type_traits>
+
 #include "score_common.h"
 #include "select_common.h"
 
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
     }
 }
 
-// Step 2: (key, column) of every score >= its row's pivot.  Segment g of a row owns slots
+// Step 2: (score, column) of every score >= its row's pivot.  Segment g of a row owns slots
 // g*kFSegCap .. of the row's kCandCap, filled in ascending column order; cand_cnt[row*kFSeg + g]
 // counts all passing scores of the segment, stored or not.
 __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* __restrict__ heads,
@@ -187,26 +189,35 @@ __global__ __launch_bounds__(256) void fused_candidates_kernel(const HeadGeom* _
         pv[a] = real[a] ? pivot[row_base + r] : INFINITY;
         base[a] = 0;
     }
-    for (int c0 = c_begin; c0 < c_end; c0 += kFC) {
-        float acc[RA][8];
-        score_block<RA>(acc, qs, ks, kbase, dp, [&](int r) { return c0 + r < nT ? c0 + r : -1; });
-        const bool full = c0 + kFC <= nT;
+    // The workgroup's rows own one contiguous piece of the candidate array: a uniform base and a
+    // 32-bit offset per store.
+    char* wg_out = reinterpret_cast<char*>(cand + (row_base + r0) * kCandCap);
+    uint32_t row_off[RA];
+#pragma unroll
+    for (int a = 0; a < RA; ++a) row_off[a] = (uint32_t)(((ti + 16 * a) * kCandCap + seg * kFSegCap) * sizeof(uint2));
+    // pass: the score is a candidate; kept in ascending column order by one ballot per column group
+    auto compact = [&](float (&acc)[RA][8], int c0, auto full) {
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
-            const int64_t out = (row_base + r0 + ti + 16 * a) * kCandCap + seg * kFSegCap;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float s = acc[a][e] * scale;
                 const int col = c0 + tj + 16 * e;
-                const bool pass = s >= pv[a] && (full || col < nT);
+                const bool pass = decltype(full)::value ? s >= pv[a] : (s >= pv[a]) & (col < nT);
                 const uint32_t mine = (uint32_t)(__ballot(pass) >> shift) & 0xffffu;
                 const int pos = base[a] + __popc(mine & below);
-                if (pass && pos < kFSegCap) {
-                    cand[out + pos] = make_uint2(score_key(s), (uint32_t)col);   // one 8-byte store
-                }
+                if (pass && pos < kFSegCap)   // the score's bits; the search turns them into a key
+                    *reinterpret_cast<uint2*>(wg_out + row_off[a] + (uint32_t)pos * sizeof(uint2)) =
+                        make_uint2(__float_as_uint(s), (uint32_t)col);
                 base[a] += __popc(mine);
             }
         }
+    };
+    for (int c0 = c_begin; c0 < c_end; c0 += kFC) {
+        float acc[RA][8];
+        score_block<RA>(acc, qs, ks, kbase, dp, [&](int r) { return c0 + r < nT ? c0 + r : -1; });
+        if (c0 + kFC <= nT) compact(acc, c0, std::true_type{});
+        else compact(acc, c0, std::false_type{});
     }
     if (tj == 0) {
 #pragma unroll
@@ -246,7 +257,7 @@ __global__ __launch_bounds__(256) void fused_finish_kernel(const HeadGeom* __res
         if (!ok) group_flags[row >> 7] = 1;
     }
     if (!ok) return;
-    // (key, column) pairs: keys at even words, columns at odd words of the row's slots
+    // (score bits, column) pairs: scores at even words, columns at odd words of the row's slots
     const uint32_t* ckey = reinterpret_cast<const uint32_t*>(cand + row * kCandCap);
     const int32_t* ccol = reinterpret_cast<const int32_t*>(cand + row * kCandCap) + 1;
     auto at = [&](int c) {   // word offset of the c-th candidate of the row
@@ -256,9 +267,9 @@ __global__ __launch_bounds__(256) void fused_finish_kernel(const HeadGeom* __res
             if (c >= seg_end[g - 1]) slot = g * kFSegCap + (c - seg_end[g - 1]);
         return 2 * slot;
     };
-    if (m_cand <= 256) select_candidates<4>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
-    else if (m_cand <= 512) select_candidates<8>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
-    else select_candidates<16>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
+    if (m_cand <= 256) select_candidates<4, true>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
+    else if (m_cand <= 512) select_candidates<8, true>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
+    else select_candidates<16, true>(ckey, ccol, m_cand, ri.k, ri.dst, lane, at);
 }
 
 constexpr int kFallbackRows = 16;

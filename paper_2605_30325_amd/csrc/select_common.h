@@ -124,15 +124,17 @@ __device__ __forceinline__ RowInfo locate_row(const HeadGeom* __restrict__ heads
 constexpr int kCandCap = 1024;
 constexpr int kSample = 256;
 
-// Candidate c (in column order) is stored at index at(c) of ckey / ccol.
-template <int NI, typename At>
+// Candidate c (in column order) is stored at index at(c) of ckey / ccol; kRawScores: ckey holds
+// the scores' bit patterns rather than their keys.
+template <int NI, bool kRawScores, typename At>
 __device__ __forceinline__ void select_candidates(const uint32_t* ckey, const int32_t* ccol, int m_cand, int k,
                                                   int32_t* __restrict__ dst, int lane, At at) {
     uint32_t key[NI];
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
         const int c = t * 64 + lane;
-        key[t] = c < m_cand ? ckey[at(c)] : 0u;
+        const uint32_t raw = c < m_cand ? ckey[at(c)] : 0u;
+        key[t] = c < m_cand ? (kRawScores ? score_key(__uint_as_float(raw)) : raw) : 0u;
     }
     uint32_t thr = 0;
     for (int bit = 31; bit >= 0; --bit) {
@@ -166,7 +168,7 @@ __device__ __forceinline__ void select_candidates(const uint32_t* ckey, const in
 template <int NI>
 __device__ __forceinline__ void select_candidates(const uint32_t* ckey, const int32_t* ccol, int m_cand, int k,
                                                   int32_t* __restrict__ dst, int lane) {
-    select_candidates<NI>(ckey, ccol, m_cand, k, dst, lane, [](int c) { return c; });
+    select_candidates<NI, false>(ckey, ccol, m_cand, k, dst, lane, [](int c) { return c; });
 }
 
 struct SampleArgs { int32_t m[kMaxHeads]; };   // pivot rank in the sample per head; 0 = no sampling
