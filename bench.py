@@ -291,6 +291,14 @@ def main():
                        "score_select": bytes_score_select}
         result["stage_hbm_gbps"] = {n: stage_bytes[n] / (ms * 1e-3) / 1e9 for n, ms in stage_ms.items() if n != "attn"}
         result["stage_hbm_frac"] = {n: g / PEAK_HBM_GBPS for n, g in result["stage_hbm_gbps"].items()}
+        # stages 2+3 are bound by their fixed-order fp32 chains (plain fma, no packed fp32: half the
+        # vector peak), not by memory: projections 2*(3d*d + d*d') flop per tile and estimator, scores
+        # 2*d' flop per tile pair
+        dp_, hid_ = int(eq.w2.shape[-1]), int(eq.w1.shape[-1])
+        chain_flops = (2 * 2 * (3 * d * hid_ + hid_ * dp_) * int(tiles.sum()) + 2 * dp_ * int((tiles * tiles).sum())) * wl.batch
+        t23 = stage_ms.get("score_select", stage_ms.get("score", 0.0) + stage_ms.get("select", 0.0))
+        result["stage23_fp32"] = {"flop": chain_flops, "tflops": chain_flops / (t23 * 1e-3) / 1e12,
+                                  "frac_of_unpacked_vector_peak": chain_flops / (t23 * 1e-3) / 1e12 / (PEAK_F32_VALU_TFLOPS / 2)}
 
     if args.dense:
         kd = np.asarray(plan.tiles, np.int32)
