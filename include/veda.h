@@ -98,7 +98,8 @@ int64_t veda_plan_tile_offset(const veda_plan*, int32_t head);/* tile_off[h] = s
 int64_t veda_plan_score_offset(const veda_plan*, int32_t head);/* sum_{h'<h} N_T[h']^2          */
 int64_t veda_plan_total_tiles(const veda_plan*);              /* sum_h N_T[h]                  */
 int64_t veda_plan_score_elems(const veda_plan*);              /* sum_h N_T[h]^2 (per batch)    */
-/* Bytes of scratch veda_tile_score needs for the given projections (descriptors + latents). */
+/* Bytes of scratch veda_tile_score needs for the given projections (descriptors, hidden layers
+ * and latents). */
 size_t veda_plan_workspace_bytes(const veda_plan*, const veda_mlp* phi_q, const veda_mlp* phi_k);
 
 /* ---- stage 1: head-aware 3D tiling (Sec. 4.2; Alg. 1 "Tiling"; Alg. 2 "Tile") ----------- */
@@ -131,8 +132,10 @@ veda_status veda_tile_score(const veda_plan*, const void* q_tiled, const void* k
  * stats   device fp32 [batch][total_tiles][3*head_dim] = [Avg|Max|Min] of every tile over its
  *         real tokens, per channel, bit-identical to the descriptors veda_tile_score derives.
  * veda_tile_score_stats = veda_tile_score starting from such descriptors (stats_q of Q, stats_k
- * of K); workspace needs batch*total_tiles*2*out_dim floats (veda_plan_workspace_bytes() is
- * enough).  scores are bit-identical to veda_tile_score on the same inputs. */
+ * of K); workspace needs batch*total_tiles*2*out_dim floats; given batch*total_tiles*(hidden_q +
+ * hidden_k) floats more (veda_plan_workspace_bytes() is enough) the hidden layers pass through
+ * it and the projections run faster.  scores are bit-identical to veda_tile_score on the same
+ * inputs either way. */
 veda_status veda_tile_layout_stats(const veda_plan*, const void* x, veda_strides sx, void* x_tiled,
                                    uint64_t* valid_mask, int32_t* valid_cnt, float* stats, void* stream);
 veda_status veda_tile_score_stats(const veda_plan*, const float* stats_q, const float* stats_k,

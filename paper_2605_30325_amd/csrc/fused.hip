@@ -297,14 +297,14 @@ __global__ __launch_bounds__(256) void fused_fallback_kernel(const HeadGeom* __r
 }
 
 struct FusedSpace {
-    float *zq, *zk, *yq, *yk, *pivot, *scratch;
+    float *zq, *zk, *yq, *yk, *hq, *hk, *pivot, *scratch;
     int32_t *cnt, *flags, *group_flags;
     uint2* cand;
     size_t bytes;
 };
 
 // Carves the workspace; with_stats also reserves the two descriptor arrays.
-static FusedSpace carve(const veda_plan* pl, int dp, bool with_stats, void* workspace) {
+static FusedSpace carve(const veda_plan* pl, int dp, int hidden_q, int hidden_k, bool with_stats, void* workspace) {
     const size_t rows = (size_t)pl->prob.batch * (size_t)pl->total_tiles;
     char* p = (char*)workspace;
     size_t off = 0;
@@ -319,6 +319,8 @@ static FusedSpace carve(const veda_plan* pl, int dp, bool with_stats, void* work
     f.zk = (float*)take(zbytes);
     f.yq = (float*)take(rows * dp * sizeof(float));
     f.yk = (float*)take(rows * dp * sizeof(float));
+    f.hq = (float*)take(rows * (size_t)hidden_q * sizeof(float));
+    f.hk = (float*)take(rows * (size_t)hidden_k * sizeof(float));
     f.pivot = (float*)take(rows * sizeof(float));
     f.cnt = (int32_t*)take(rows * kFSeg * sizeof(int32_t));
     f.flags = (int32_t*)take(rows * sizeof(int32_t));
@@ -340,7 +342,8 @@ static veda_status score_select(const veda_plan* pl, const veda_mlp* phi_q, cons
     int max_tiles;
     if (!select_setup(pl, k_per_head, args, sample, sampled, max_tiles)) return VEDA_ERR_INVALID_ARG;
     if (args.nnz_per_batch * pl->prob.batch >= ((int64_t)1 << 31)) return VEDA_ERR_UNSUPPORTED;  // row_ptr is int32
-    veda_status st = launch_projections(pl, phi_q, phi_k, zq, zk, f.yq, f.yk, s);
+    veda_status st = launch_projections(pl, phi_q, phi_k, zq, zk, f.yq, f.yk, phi_q->hidden ? f.hq : nullptr,
+                                        phi_k->hidden ? f.hk : nullptr, s);
     if (st != VEDA_OK) return st;
     if (!sampled || dp > kFMaxDp) {   // the two-stage route, through the scratch matrix
         st = launch_score_blocks(pl, f.yq, f.yk, f.scratch, dp, scale, nullptr, s);
@@ -378,7 +381,7 @@ static veda_status check_pair(const veda_plan* pl, const veda_mlp* phi_q, const 
 
 extern "C" size_t veda_plan_fused_workspace_bytes(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k) {
     if (!pl || !phi_q || !phi_k || phi_q->out_dim < 1) return 0;
-    return veda::carve(pl, phi_q->out_dim, true, nullptr).bytes;
+    return veda::carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, nullptr).bytes;
 }
 
 extern "C" veda_status veda_tile_score_select(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
@@ -391,7 +394,7 @@ extern "C" veda_status veda_tile_score_select(const veda_plan* pl, const void* q
     const veda_status st = check_pair(pl, phi_q, phi_k);
     if (st != VEDA_OK) return st;
     if (!aligned16(q_tiled) || !aligned16(k_tiled) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
-    const FusedSpace f = carve(pl, phi_q->out_dim, true, workspace);
+    const FusedSpace f = carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, workspace);
     if (!workspace || workspace_bytes < f.bytes) return VEDA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     launch_trippool(pl, q_tiled, k_tiled, valid_mask, f.zq, f.zk, s);
@@ -409,7 +412,7 @@ extern "C" veda_status veda_tile_score_select_stats(const veda_plan* pl, const f
     const veda_status st = check_pair(pl, phi_q, phi_k);
     if (st != VEDA_OK) return st;
     if (!aligned16(stats_q) || !aligned16(stats_k) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
-    const FusedSpace f = carve(pl, phi_q->out_dim, true, workspace);
+    const FusedSpace f = carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, workspace);
     if (!workspace || workspace_bytes < f.bytes) return VEDA_ERR_WORKSPACE;
     return score_select(pl, phi_q, phi_k, scale, stats_q, stats_k, k_per_head, row_ptr, col_idx, f, (hipStream_t)stream);
 }

@@ -215,7 +215,9 @@ int64_t veda_plan_score_elems(const veda_plan* pl) { return pl ? pl->score_elems
 size_t veda_plan_workspace_bytes(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k) {
     if (!pl || !phi_q || !phi_k) return 0;
     const size_t rows = (size_t)pl->prob.batch * (size_t)pl->total_tiles;
-    const size_t per_row = (size_t)(2 * 3 * pl->prob.head_dim + phi_q->out_dim + phi_k->out_dim);
+    // descriptors of Q and K, latents, and the hidden layers of the two projections
+    const size_t per_row = (size_t)(2 * 3 * pl->prob.head_dim + phi_q->out_dim + phi_k->out_dim) +
+                           (size_t)(phi_q->hidden > 0 ? phi_q->hidden : 0) + (size_t)(phi_k->hidden > 0 ? phi_k->hidden : 0);
     return ((rows * per_row * sizeof(float)) + 255) / 256 * 256;
 }
 

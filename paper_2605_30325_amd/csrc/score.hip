@@ -215,9 +215,11 @@ __global__ __launch_bounds__(kMlpThreads, 4) void mlp_kernel(const HeadGeom* __r
                                                          const int32_t* __restrict__ row_blk,
                                                          const float* __restrict__ zq, const float* __restrict__ zk,
                                                          float* __restrict__ yq, float* __restrict__ yk,
-                                                         MlpDev pq, MlpDev pk, int64_t total_tiles) {
+                                                         MlpDev pq, MlpDev pk, int64_t total_tiles,
+                                                         float* __restrict__ hq, float* __restrict__ hk) {
     extern __shared__ __align__(16) float smem[];
     const MlpDev p = blockIdx.y == 0 ? pq : pk;
+    float* hglb = blockIdx.y == 0 ? hq : hk;   // hidden layer kept in global scratch instead of LDS, if given
     const float* z = blockIdx.y == 0 ? zq : zk;
     float* y = blockIdx.y == 0 ? yq : yk;
     float* ws = smem;                                   // 2 x [16][128]
@@ -230,7 +232,16 @@ __global__ __launch_bounds__(kMlpThreads, 4) void mlp_kernel(const HeadGeom* __r
     const int64_t row0 = (int64_t)blockIdx.z * total_tiles + hg.tile_off + (int64_t)blk * kMlpRows;
     const float* x = z + row0 * p.in_dim;
     float* out = y + row0 * p.out_dim;
-    if (p.hidden) {
+    if (p.hidden && hglb) {
+        // The 64 x hidden intermediate goes through global memory (it stays in L2): without it in
+        // LDS twice as many workgroups fit on a compute unit.  The barrier that opens the second
+        // layer also orders these stores before its loads (same workgroup).
+        float* hrow = hglb + row0 * p.hidden;
+        mlp_layer<true, false>(x, nullptr, 0, rows, p.in_dim, p.w1 + (int64_t)head * p.in_dim * p.hidden,
+                  p.b1 + (int64_t)head * p.hidden, p.hidden, p.relu != 0, nullptr, 0, hrow, xs, ws);
+        mlp_layer<true, false>(hrow, nullptr, 0, rows, p.hidden, p.w2 + (int64_t)head * p.hidden * p.out_dim,
+                  p.b2 + (int64_t)head * p.out_dim, p.out_dim, false, nullptr, 0, out, xs, ws);
+    } else if (p.hidden) {
         const int ldh = (p.hidden + 3) & ~3;
         mlp_layer<true, true>(x, nullptr, 0, rows, p.in_dim, p.w1 + (int64_t)head * p.in_dim * p.hidden,
                   p.b1 + (int64_t)head * p.hidden, p.hidden, p.relu != 0, hs, ldh, nullptr, xs, ws);
@@ -415,17 +426,19 @@ __global__ __launch_bounds__(256) void closed_form_latent_kernel(const float* __
 
 // Projections (Eq. 5 phi_q, phi_k) of the descriptors zq, zk into the latents yq, yk.
 veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, const float* zq,
-                               const float* zk, float* yq, float* yk, hipStream_t s) {
+                               const float* zk, float* yq, float* yk, float* hq, float* hk, hipStream_t s) {
     MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
     MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
     const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
+    // the global route reads the hidden layer back as float4 rows
+    if (!hq || !hk || (phi_q->hidden & 3) || (phi_k->hidden & 3)) hq = hk = nullptr;
     const size_t smem = sizeof(float) * ((size_t)2 * kMlpWsFloats + (size_t)2 * kMlpXsFloats +
-                                         (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3));
+                                         (hq ? 0 : (size_t)kMlpRows * (size_t)((max_hidden + 3) & ~3)));
     if (smem > 64 * 1024)
         VEDA_HIP_TRY(hipFuncSetAttribute((const void*)mlp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     dim3 mgrid((unsigned)pl->row_blocks, 2, (unsigned)pl->prob.batch);
     hipLaunchKernelGGL(mlp_kernel, mgrid, dim3(kMlpThreads), smem, s, pl->d_heads, pl->d_row_blk, zq, zk, yq,
-                       yk, pq, pk, pl->total_tiles);
+                       yk, pq, pk, pl->total_tiles, hq, hk);
     return launch_status("mlp_kernel");
 }
 
@@ -446,10 +459,11 @@ veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const floa
     return launch_status("score_kernel");
 }
 
+// hq, hk: scratch for the hidden layers, or null.
 static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
-                                     const float* zq, const float* zk, float* yq, float* yk, float* scores,
-                                     hipStream_t s) {
-    const veda_status st = launch_projections(pl, phi_q, phi_k, zq, zk, yq, yk, s);
+                                     const float* zq, const float* zk, float* yq, float* yk, float* hq, float* hk,
+                                     float* scores, hipStream_t s) {
+    const veda_status st = launch_projections(pl, phi_q, phi_k, zq, zk, yq, yk, hq, hk, s);
     if (st != VEDA_OK) return st;
     return launch_score_blocks(pl, yq, yk, scores, phi_q->out_dim, scale, nullptr, s);
 }
@@ -475,13 +489,15 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     float* zk = zq + rows * 3 * d;
     float* yq = zk + rows * 3 * d;
     float* yk = yq + rows * dp;
+    float* hq = yk + rows * dp;               // the plan's workspace size has room for both hidden layers
+    float* hk = hq + rows * (phi_q->hidden > 0 ? phi_q->hidden : 0);
     hipStream_t s = (hipStream_t)stream;
 
     launch_trippool(pl, q_tiled, k_tiled, valid_mask, zq, zk, s);
     st = launch_status("trippool_kernel");
     if (st != VEDA_OK) return st;
 
-    return project_and_score(pl, phi_q, phi_k, scale, zq, zk, yq, yk, scores, s);
+    return project_and_score(pl, phi_q, phi_k, scale, zq, zk, yq, yk, hq, hk, scores, s);
 }
 
 extern "C" veda_status veda_tile_score_stats(const veda_plan* pl, const float* stats_q, const float* stats_k,
@@ -500,7 +516,13 @@ extern "C" veda_status veda_tile_score_stats(const veda_plan* pl, const float* s
     if (!workspace || workspace_bytes < sizeof(float) * (size_t)rows * 2 * (size_t)dp) return VEDA_ERR_WORKSPACE;
     float* yq = (float*)workspace;
     float* yk = yq + rows * dp;
-    return project_and_score(pl, phi_q, phi_k, scale, stats_q, stats_k, yq, yk, scores, (hipStream_t)stream);
+    // with room for them the hidden layers go through the workspace too (twice the workgroups per
+    // compute unit); the results are the same either way
+    const size_t hid = (size_t)(phi_q->hidden > 0 ? phi_q->hidden : 0) + (size_t)(phi_k->hidden > 0 ? phi_k->hidden : 0);
+    const bool roomy = workspace_bytes >= sizeof(float) * (size_t)rows * (2 * (size_t)dp + hid);
+    float* hq = roomy ? yk + rows * dp : nullptr;
+    float* hk = roomy ? hq + rows * (phi_q->hidden > 0 ? phi_q->hidden : 0) : nullptr;
+    return project_and_score(pl, phi_q, phi_k, scale, stats_q, stats_k, yq, yk, hq, hk, scores, (hipStream_t)stream);
 }
 
 extern "C" veda_status veda_tile_score_closed_form(const veda_plan* pl, const void* q_tiled, const void* k_tiled,

@@ -16,8 +16,10 @@ void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_til
                      float* zq, float* zk, hipStream_t s);
 
 // phi_q, phi_k (Eq. 5) of the descriptors into the latents yq, yk ([rows][out_dim] fp32 each).
+// hq, hk: optional scratch of [rows][hidden] floats each for the hidden layers (else they stay
+// in LDS, which halves the workgroups resident per compute unit).
 veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, const float* zq,
-                               const float* zk, float* yq, float* yk, hipStream_t s);
+                               const float* zk, float* yq, float* yk, float* hq, float* hk, hipStream_t s);
 
 // The score blocks of all heads (Eq. 5) from latents of dp coordinates.  marks != nullptr: one
 // mark per 128 consecutive rows of the latents (row >> 7); only the score rows of 128-row blocks

@@ -263,10 +263,10 @@ def veda_tile_score_stats(plan: Plan, stats_q, stats_k, phi_q: Mlp, phi_k: Mlp, 
     dev = stats_q.device
     if scores is None:
         scores = torch.empty((plan.batch, plan.score_elems), dtype=torch.float32, device=dev)
-    need = plan.batch * plan.total_tiles * 2 * phi_q.out_dim * 4
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     sq, sk = phi_q.struct(), phi_k.struct()
+    if workspace is None:   # room for the hidden layers too: the faster route of the projections
+        need = int(load().veda_plan_workspace_bytes(plan.handle, C.byref(sq), C.byref(sk)))
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     _check(load().veda_tile_score_stats(plan.handle, _ptr(stats_q), _ptr(stats_k), C.byref(sq), C.byref(sk),
                                         C.c_float(scale), _ptr(scores), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()),
