@@ -98,11 +98,12 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
                                                           const int32_t* __restrict__ row_blk,
                                                           const float* __restrict__ yq, const float* __restrict__ yk,
                                                           int dp, float scale, int64_t total_tiles, SampleArgs sample,
-                                                          float* __restrict__ pivot, int32_t* __restrict__ group_flags) {
-    // first the operand stages of the two sample blocks, then the 64 x 256 sample scores
-    __shared__ __align__(16) float smem[kFR * kSample];
-    float* qs = smem;
-    float* ks = smem + kFR * kFQPitch;
+                                                          float* __restrict__ pivot, int32_t* __restrict__ group_flags,
+                                                          float* __restrict__ samples) {
+    // The 64 x 256 sample scores go through global scratch (they stay in L2) rather than LDS: with
+    // only the operand stages in LDS four workgroups fit on a compute unit instead of two.
+    __shared__ __align__(16) float qs[kFR * kFQPitch];
+    __shared__ __align__(16) float ks[kFC * kFKPitch];
     const int32_t code = row_blk[blockIdx.x];
     const int head = code >> 24, r0 = (code & 0xffffff) * kFR;
     const HeadGeom hg = heads[head];
@@ -118,15 +119,17 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
     for (int sb = 0; sb < 2; ++sb)
         score_block<4>(acc[sb], qs, ks, kbase, dp,
                        [&](int r) { return (int)(((int64_t)(sb * kFC + r) * nT) / kSample); });
-    __syncthreads();
     const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
+    float* smp = samples + (row_base + r0) * kSample;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+    for (int a = 0; a < 4; ++a) {
+        if (r0 + ti + 16 * a >= nT) continue;   // rows past the head belong to another workgroup
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) smem[(ti + 16 * a) * kSample + sb * kFC + tj + 16 * e] = acc[sb][a][e] * scale;
-    __syncthreads();
+            for (int e = 0; e < 8; ++e) smp[(ti + 16 * a) * kSample + sb * kFC + tj + 16 * e] = acc[sb][a][e] * scale;
+    }
+    __syncthreads();   // orders the stores before the loads below (same workgroup)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = sample.m[head];
     for (int rr = 0; rr < kFR / 4; ++rr) {
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(256) void fused_pivot_kernel(const HeadGeom* __rest
         if (r0 + r >= nT) break;
         uint32_t sk[kSample / 64];
 #pragma unroll
-        for (int e = 0; e < kSample / 64; ++e) sk[e] = score_key(smem[r * kSample + e * 64 + lane]);
+        for (int e = 0; e < kSample / 64; ++e) sk[e] = score_key(smp[r * kSample + e * 64 + lane]);
         // Any pivot with at least k scores above it serves: the search stops after the top 20 key
         // bits, which leaves the pivot at or just below the sample's m-th largest value.
         uint32_t pk = 0;
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(256) void fused_fallback_kernel(const HeadGeom* __r
 }
 
 struct FusedSpace {
-    float *zq, *zk, *yq, *yk, *hq, *hk, *pivot, *scratch;
+    float *zq, *zk, *yq, *yk, *hq, *hk, *pivot, *samples, *scratch;
     int32_t *cnt, *flags, *group_flags;
     uint2* cand;
     size_t bytes;
@@ -322,6 +325,7 @@ static FusedSpace carve(const veda_plan* pl, int dp, int hidden_q, int hidden_k,
     f.hq = (float*)take(rows * (size_t)hidden_q * sizeof(float));
     f.hk = (float*)take(rows * (size_t)hidden_k * sizeof(float));
     f.pivot = (float*)take(rows * sizeof(float));
+    f.samples = (float*)take(rows * kSample * sizeof(float));
     f.cnt = (int32_t*)take(rows * kFSeg * sizeof(int32_t));
     f.flags = (int32_t*)take(rows * sizeof(int32_t));
     f.group_flags = (int32_t*)take((rows / 128 + 2) * sizeof(int32_t));
@@ -354,7 +358,7 @@ static veda_status score_select(const veda_plan* pl, const veda_mlp* phi_q, cons
     dim3 bgrid((unsigned)pl->row_blocks, (unsigned)pl->prob.batch), rgrid((unsigned)((rows + 3) / 4)), block(256);
     dim3 cgrid((unsigned)pl->row_blocks, (unsigned)(pl->prob.batch * kFSeg));
     hipLaunchKernelGGL(fused_pivot_kernel, bgrid, block, 0, s, pl->d_heads, pl->d_row_blk, f.yq, f.yk, dp, scale,
-                       pl->total_tiles, sample, f.pivot, f.group_flags);
+                       pl->total_tiles, sample, f.pivot, f.group_flags, f.samples);
     if ((st = launch_status("fused_pivot_kernel")) != VEDA_OK) return st;
     hipLaunchKernelGGL(fused_candidates_kernel, cgrid, block, 0, s, pl->d_heads, pl->d_row_blk, f.yq, f.yk, dp, scale,
                        pl->total_tiles, f.pivot, f.cand, f.cnt);
