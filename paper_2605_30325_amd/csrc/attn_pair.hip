@@ -190,7 +190,7 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
 }
 
 // After the last step: normalise, transpose through LDS and scatter the real rows of the
-// workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, lse_s after it.
+// workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, then lse_s and tok_s.
 template <int D>
 __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnArgs& a, const HeadGeom& hg, char* smem,
                                             int head, int qiA, int qiB, bool hasB, int64_t b, int tid, int which,
@@ -200,7 +200,10 @@ __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnAr
     const float inv = l_all > 0.0f ? 1.0f / l_all : 0.0f;
     char* obuf = smem;
     float* lse_s = reinterpret_cast<float*>(smem + 2 * kTile * kRowB);   // [2][64]
+    int* tok_s = reinterpret_cast<int*>(lse_s + 2 * kTile);              // [2][64] token of each row, -1 = padding
     __syncthreads();
+    // the slot -> token map costs a handful of integer divisions: once per row, not once per chunk
+    if (tid < 2 * kTile) tok_s[tid] = slot_token(hg, tid / kTile ? qiB : qiA, tid % kTile, a.T, a.H, a.W);
     {
         char* orow = obuf + (which * kTile + 32 * r + lq) * kRowB;
 #pragma unroll
@@ -221,13 +224,13 @@ __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnAr
     const int n_tiles = hasB ? 2 : 1;
     for (int cid = tid; cid < n_tiles * kTile * kKChunks; cid += 256) {
         const int row = cid / kKChunks, ch = cid % kKChunks;
-        const int n = slot_token(hg, row / kTile ? qiB : qiA, row % kTile, a.T, a.H, a.W);
+        const int n = tok_s[row];
         if (n >= 0)
             *reinterpret_cast<uint4*>(ob + (int64_t)n * a.so_n + ch * 16) =
                 *reinterpret_cast<const uint4*>(obuf + row * kRowB + ch * 16);
     }
     if (a.lse && tid < n_tiles * kTile) {
-        const int n = slot_token(hg, tid / kTile ? qiB : qiA, tid % kTile, a.T, a.H, a.W);
+        const int n = tok_s[tid];
         if (n >= 0) a.lse[(b * a.n_heads + head) * a.tokens + n] = lse_s[tid];
     }
 }
