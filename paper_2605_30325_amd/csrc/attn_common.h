@@ -44,8 +44,11 @@ __device__ inline bool xcd_work(const int32_t* __restrict__ xcd_cum, const HeadG
     const int x = blockIdx.x % kXcd, local = blockIdx.x / kXcd;
     const int32_t* cum = xcd_cum + x * (n_heads + 1);
     if (local >= cum[n_heads]) return false;
-    int h = 0;
-    while (local >= cum[h + 1]) ++h;
+    int h = 0, hi = n_heads - 1;   // the last head whose first item is <= local: log2(heads) dependent loads
+    while (h < hi) {
+        const int mid = (h + hi + 1) >> 1;
+        if (local >= cum[mid]) h = mid; else hi = mid - 1;
+    }
     const int n = unit == 2 ? heads[h].n_pairs : heads[h].n_tiles;
     head = h;
     item = x * (n / kXcd) + (x < n % kXcd ? x : n % kXcd) + (local - cum[h]);
