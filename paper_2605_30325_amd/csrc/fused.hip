@@ -4,7 +4,7 @@
 // The N_T x N_T scores of a head are formed block by block exactly as score.hip forms them (one
 // fmaf chain per score over ascending latent coordinate from +0, then one multiply by scale),
 // but instead of being written out each score is compared with a pivot of its row, and only the
-// few that pass leave the compute unit, as (key, column) candidates in column order.  The exact
+// few that pass leave the compute unit, as (score, column) candidates in column order.  The exact
 // top-k of a row is then the exact top-k of its candidates:
 //   1. fused_pivot_kernel: per row, the scores of 256 evenly spread columns; the pivot is their
 //      m-th largest (m per head from the host, a few standard deviations above 256*k/n).
