@@ -46,6 +46,10 @@ def parse():
                     help="stages 2 and 3 as separate calls with the score matrix between them; default: one call "
                          "(veda_tile_score_select*, scores never written), whose time is reported under stage "
                          "'score' with stage 'select' 0")
+    ap.add_argument("--tiled-q", action="store_true",
+                    help="write the tiled copy of Q and let the attention kernel read it; default (bf16, 64-token "
+                         "tiles, descriptors from the gather): Q's gather only takes descriptors and masks, the "
+                         "attention kernel gathers Q rows from token order itself")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
     ap.add_argument("--tile-tokens", type=int, default=64, choices=(64, 128),
@@ -185,6 +189,10 @@ def main():
     bytes_score_select = bytes_score - int((tiles * tiles).sum()) * 4 * wl.batch + pairs * 4
     bytes_attn_kv = pairs * 2 * B * d * es
 
+    # Q straight from token order: needs the descriptor-taking gather (64-token tiles) and the bf16 kernel
+    q_from_tokens = not args.tiled_q and not args.unfused and wl.dtype == "bf16"
+    if q_from_tokens:
+        bytes_layout -= slots * d * es   # the tiled copy of Q is not written
     bufs = {}
 
     def step(events=None):
@@ -194,7 +202,8 @@ def main():
             qt, vm, vc = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
             kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, bufs.get("kt"), want_mask=False)
         else:   # TripPool descriptors taken during the Q and K gathers
-            qt, vm, vc, zq = veda.veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"), bufs.get("zq"))
+            qt, vm, vc, zq = veda.veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"),
+                                                         bufs.get("zq"), want_tiles=not q_from_tokens)
             kt, _, _, zk = veda.veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False)
             bufs.update(zq=zq, zk=zk)
         vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
@@ -218,14 +227,15 @@ def main():
             if ev: ev[2].record()
             rp, ci = veda.veda_tile_select(plan, s, kph, bufs.get("rp"), bufs.get("ci"))
         if ev: ev[3].record()
-        out, _ = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
+        out, _ = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"),
+                                           q_tokens=q if q_from_tokens else None)
         if ev: ev[4].record()
         bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)
 
     def attn_only(events=None):
         if events: events[3].record()
         veda.veda_sparse_attn_fwd(plan, bufs["qt"], bufs["kt"], bufs["vt"], bufs["vm"], bufs["rp"], bufs["ci"],
-                                  softmax_scale, bufs["out"])
+                                  softmax_scale, bufs["out"], q_tokens=q if q_from_tokens else None)
         if events: events[4].record()
 
     step()
@@ -299,6 +309,9 @@ def main():
         t23 = stage_ms.get("score_select", stage_ms.get("score", 0.0) + stage_ms.get("select", 0.0))
         result["stage23_fp32"] = {"flop": chain_flops, "tflops": chain_flops / (t23 * 1e-3) / 1e12,
                                   "frac_of_unpacked_vector_peak": chain_flops / (t23 * 1e-3) / 1e12 / (PEAK_F32_VALU_TFLOPS / 2)}
+
+    if (args.dense or args.heatmap) and bufs.get("qt") is None:   # these side runs read the tiled Q
+        bufs["qt"] = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR, want_mask=False)[0]
 
     if args.dense:
         kd = np.asarray(plan.tiles, np.int32)

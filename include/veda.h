@@ -131,6 +131,7 @@ veda_status veda_tile_score(const veda_plan*, const void* q_tiled, const void* k
 /* veda_tile_layout_stats = veda_tile_layout(VEDA_TOKEN_MAJOR) that also writes
  * stats   device fp32 [batch][total_tiles][3*head_dim] = [Avg|Max|Min] of every tile over its
  *         real tokens, per channel, bit-identical to the descriptors veda_tile_score derives.
+ *         x_tiled may be NULL: descriptors (and masks) only.
  * veda_tile_score_stats = veda_tile_score starting from such descriptors (stats_q of Q, stats_k
  * of K); workspace needs batch*total_tiles*2*out_dim floats; given batch*total_tiles*(hidden_q +
  * hidden_k) floats more (veda_plan_workspace_bytes() is enough) the hidden layers pass through
@@ -205,6 +206,14 @@ veda_status veda_sparse_attn_fwd(const veda_plan*, const void* q_tiled, const vo
                                  const void* v_tiled, const uint64_t* valid_mask,
                                  const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
                                  void* out, veda_strides so, float* lse, void* stream);
+/* The same with Q taken straight from token order (q, strides sq; bf16 plans only): the kernel
+ * gathers each query tile's rows itself, so the tiled copy of Q need not be written at all
+ * (veda_tile_layout_stats with x_tiled = NULL still gives its descriptors and the masks).
+ * Results are bit-identical to veda_sparse_attn_fwd on the tiled Q. */
+veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan*, const void* q, veda_strides sq, const void* k_tiled,
+                                          const void* v_tiled, const uint64_t* valid_mask,
+                                          const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
+                                          void* out, veda_strides so, float* lse, void* stream);
 
 /* ---- supervision side: target tile scores of full attention and tile recall ------------- */
 /* veda_tile_heatmap (Sec. 4.1 Eq. 3; Sec. 4.3 "Efficient Ground-Truth Heatmap Generation"):

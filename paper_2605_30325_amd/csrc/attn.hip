@@ -106,19 +106,24 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a, float 
 
 }  // namespace veda
 
-extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
-                                            const void* v_tiled, const uint64_t* valid_mask,
-                                            const int32_t* row_ptr, const int32_t* col_idx,
-                                            float softmax_scale, void* out, veda_strides so, float* lse,
-                                            void* stream) {
-    using namespace veda;
-    if (!pl || !q_tiled || !k_tiled || !v_tiled || !valid_mask || !row_ptr || !col_idx || !out)
+namespace veda {
+
+// Shared by the two entry points: q_tiled or (q_tok, sq), not both.
+static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const void* q_tok, veda_strides sq,
+                               const void* k_tiled, const void* v_tiled, const uint64_t* valid_mask,
+                               const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale, void* out,
+                               veda_strides so, float* lse, void* stream) {
+    if (!pl || (!q_tiled && !q_tok) || !k_tiled || !v_tiled || !valid_mask || !row_ptr || !col_idx || !out)
         return VEDA_ERR_INVALID_ARG;
     if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return VEDA_ERR_INVALID_ARG;
     const int es = pl->elem_size(), d = pl->prob.head_dim;
     if (so.n < d || so.b < 0 || so.h < 0) return VEDA_ERR_INVALID_ARG;
-    if (!aligned16(q_tiled) || !aligned16(k_tiled) || !aligned16(v_tiled) || !aligned16(out) ||
+    if (q_tok && (sq.n < d || sq.b < 0 || sq.h < 0)) return VEDA_ERR_INVALID_ARG;
+    if ((q_tiled && !aligned16(q_tiled)) || !aligned16(k_tiled) || !aligned16(v_tiled) || !aligned16(out) ||
         (so.b * es) % 16 || (so.h * es) % 16 || (so.n * es) % 16)
+        return VEDA_ERR_UNSUPPORTED;
+    if (q_tok && (!aligned16(q_tok) || (sq.b * es) % 16 || (sq.h * es) % 16 || (sq.n * es) % 16 ||
+                  pl->prob.dtype != VEDA_BF16))
         return VEDA_ERR_UNSUPPORTED;
     // 128-token tiles: the kernel works on the 64-slot halves (inner plan), the CSR on whole tiles
     const veda_plan* ip = pl->inner ? pl->inner : pl;
@@ -126,6 +131,8 @@ extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_t
     a.heads = ip->d_heads;
     a.tile_head = ip->d_tile_head;
     a.q = (const char*)q_tiled; a.k = (const char*)k_tiled; a.v = (const char*)v_tiled;
+    a.q_tok = (const char*)q_tok;
+    a.sq_b = sq.b * es; a.sq_h = sq.h * es; a.sq_n = sq.n * es;
     a.valid_mask = valid_mask; a.row_ptr = row_ptr; a.col_idx = col_idx;
     a.out = (char*)out; a.lse = lse;
     a.total_tiles = ip->total_tiles;
@@ -144,4 +151,26 @@ extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_t
     if (d == 128) hipLaunchKernelGGL(sparse_attn_f32_kernel<128>, grid, block, 0, s, a, softmax_scale);
     else hipLaunchKernelGGL(sparse_attn_f32_kernel<64>, grid, block, 0, s, a, softmax_scale);
     return launch_status("veda_sparse_attn_fwd");
+}
+
+}  // namespace veda
+
+extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
+                                            const void* v_tiled, const uint64_t* valid_mask,
+                                            const int32_t* row_ptr, const int32_t* col_idx,
+                                            float softmax_scale, void* out, veda_strides so, float* lse,
+                                            void* stream) {
+    if (!q_tiled) return VEDA_ERR_INVALID_ARG;
+    return veda::sparse_attn(pl, q_tiled, nullptr, veda_strides{0, 0, 0}, k_tiled, v_tiled, valid_mask, row_ptr,
+                             col_idx, softmax_scale, out, so, lse, stream);
+}
+
+extern "C" veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan* pl, const void* q, veda_strides sq,
+                                                     const void* k_tiled, const void* v_tiled,
+                                                     const uint64_t* valid_mask, const int32_t* row_ptr,
+                                                     const int32_t* col_idx, float softmax_scale, void* out,
+                                                     veda_strides so, float* lse, void* stream) {
+    if (!q) return VEDA_ERR_INVALID_ARG;
+    return veda::sparse_attn(pl, nullptr, q, sq, k_tiled, v_tiled, valid_mask, row_ptr, col_idx, softmax_scale, out,
+                             so, lse, stream);
 }

@@ -16,7 +16,9 @@ struct AttnArgs {
     const HeadGeom* heads;
     const uint8_t* tile_head;
     const int32_t* xcd_cum;
-    const char* q;
+    const char* q;             // tiled Q, or null when q_tok is given
+    const char* q_tok;         // Q in token order (bf16 kernel only): gathered by the kernel itself
+    int64_t sq_b, sq_h, sq_n;  // its strides in bytes
     const char* k;
     const char* v;
     const uint64_t* valid_mask;

@@ -288,12 +288,22 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     // Q operand (B matrix of S^T = K Q^T): lane holds query row 32r+lq, channels 16t+8hh..+8.
     PairState<D> st;
     {
-        const char* qrow = a.q + (head_tile0 + qi) * kKBytes + (32 * r + lq) * kRowB + 16 * hh;
+        // from the tiled tensor, or straight from token order (a padded slot reads as zeros, which is
+        // what the tiled tensor holds there)
+        const char* qrow;
+        bool real = true;
+        if (a.q_tok) {
+            const int n = slot_token(hg, qi, 32 * r + lq, a.T, a.H, a.W);
+            real = n >= 0;
+            qrow = a.q_tok + b * a.sq_b + head * a.sq_h + (int64_t)(real ? n : 0) * a.sq_n + 16 * hh;
+        } else {
+            qrow = a.q + (head_tile0 + qi) * kKBytes + (32 * r + lq) * kRowB + 16 * hh;
+        }
 #pragma unroll
         for (int t = 0; t < G; ++t) {
             const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + 32 * t);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.qf[t][e] = (__bf16)((float)raw[e] * a.scale_log2);
+            for (int e = 0; e < 8; ++e) st.qf[t][e] = real ? (__bf16)((float)raw[e] * a.scale_log2) : (__bf16)0.0f;
         }
     }
 #pragma unroll

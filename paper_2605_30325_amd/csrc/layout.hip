@@ -103,8 +103,9 @@ __global__ void valid_cnt_pairs_kernel(const uint64_t* __restrict__ mask, int32_
 // the sum is the same slot-ascending fp32 chain the scoring stage uses, so the descriptors are
 // bit-identical to the ones it derives from the tiled tensor.  A workgroup holds 256 / (D / kN)
 // consecutive global tiles (they may belong to different heads).
+// kWrite = false: descriptors (and masks) only, the tiled tensor is not written.
 #pragma clang fp contract(off)
-template <typename E, int D>
+template <typename E, int D, bool kWrite>
 __global__ __launch_bounds__(256) void layout_stats_kernel(
     const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
     const char* __restrict__ x, int64_t sb, int64_t sh, int64_t sn, char* __restrict__ out,
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(256) void layout_stats_kernel(
                 mn[j] = f[j] < mn[j] ? f[j] : mn[j];
             }
         }
-        *reinterpret_cast<uint4*>(ob + l * kRowBytes) = v;
+        if (kWrite) *reinterpret_cast<uint4*>(ob + l * kRowBytes) = v;
     }
     const int cnt = __popcll(mask);
     const float inv = recip.v[cnt];
@@ -218,12 +219,12 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
                                               uint64_t* valid_mask, int32_t* valid_cnt, float* stats,
                                               void* stream) {
     using namespace veda;
-    if (!pl || !x || !x_tiled || !stats) return VEDA_ERR_INVALID_ARG;
+    if (!pl || !x || !stats) return VEDA_ERR_INVALID_ARG;   // x_tiled may be null: descriptors only
     if (pl->inner) return VEDA_ERR_UNSUPPORTED;   // 64-token tiles only
     const int es = pl->elem_size();
     const int d = pl->prob.head_dim;
     if (sx.n < d || sx.b < 0 || sx.h < 0) return VEDA_ERR_INVALID_ARG;
-    if (!aligned16(x) || !aligned16(x_tiled) || !aligned16(stats) || (sx.b * es) % 16 || (sx.h * es) % 16 ||
+    if (!aligned16(x) || (x_tiled && !aligned16(x_tiled)) || !aligned16(stats) || (sx.b * es) % 16 || (sx.h * es) % 16 ||
         (sx.n * es) % 16)
         return VEDA_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
@@ -236,9 +237,14 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
     do {                                                                                                  \
         constexpr int tiles = 256 / (D / Chunk<E>::kN);                                                   \
         dim3 grid((unsigned)((pl->total_tiles + tiles - 1) / tiles), (unsigned)pl->prob.batch);           \
-        hipLaunchKernelGGL((layout_stats_kernel<E, D>), grid, dim3(256), 0, st, pl->d_heads,              \
-                           pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, stats,            \
-                           pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                       \
+        if (x_tiled)                                                                                      \
+            hipLaunchKernelGGL((layout_stats_kernel<E, D, true>), grid, dim3(256), 0, st, pl->d_heads,    \
+                               pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, stats,        \
+                               pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                   \
+        else                                                                                              \
+            hipLaunchKernelGGL((layout_stats_kernel<E, D, false>), grid, dim3(256), 0, st, pl->d_heads,   \
+                               pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)nullptr, stats,        \
+                               pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                   \
     } while (0)
     if (es == 2 && d == 128) VEDA_LAUNCH_LS(uint16_t, 128);
     else if (es == 2 && d == 64) VEDA_LAUNCH_LS(uint16_t, 64);

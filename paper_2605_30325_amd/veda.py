@@ -27,7 +27,8 @@ EXPORTS = (
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
-    "veda_tile_score_select", "veda_tile_score_select_stats", "veda_sparse_attn_fwd", "veda_tile_heatmap",
+    "veda_tile_score_select", "veda_tile_score_select_stats", "veda_sparse_attn_fwd", "veda_sparse_attn_fwd_q_tokens",
+    "veda_tile_heatmap",
     "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
 
@@ -103,6 +104,9 @@ def load():
     L.veda_tile_score_select_stats.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
     L.veda_sparse_attn_fwd.restype = C.c_int
+    L.veda_sparse_attn_fwd_q_tokens.argtypes = [vp, vp, veda_strides, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides,
+                                                vp, vp]
+    L.veda_sparse_attn_fwd_q_tokens.restype = C.c_int
     L.veda_tile_heatmap.argtypes = [vp, vp, vp, vp, C.c_float, vp, i64, vp, vp]
     L.veda_tile_heatmap.restype = C.c_int
     L.veda_tile_recall.argtypes = [vp, C.POINTER(i32), vp, vp, vp, vp, C.c_size_t, vp]
@@ -240,11 +244,12 @@ def veda_tile_score(plan: Plan, q_tiled, k_tiled, valid_mask, phi_q: Mlp, phi_k:
 
 def veda_tile_layout_stats(plan: Plan, x: torch.Tensor, x_tiled: Optional[torch.Tensor] = None,
                            valid_mask: Optional[torch.Tensor] = None, valid_cnt: Optional[torch.Tensor] = None,
-                           stats: Optional[torch.Tensor] = None, want_mask: bool = True):
+                           stats: Optional[torch.Tensor] = None, want_mask: bool = True, want_tiles: bool = True):
     """Stage 1 (token-major) with the TripPool descriptors taken during the gather.
-    Returns (x_tiled, valid_mask, valid_cnt, stats fp32 [batch, total_tiles, 3*d])."""
+    Returns (x_tiled, valid_mask, valid_cnt, stats fp32 [batch, total_tiles, 3*d]).
+    want_tiles=False: descriptors (and masks) only, x_tiled is returned as None."""
     dev = x.device
-    if x_tiled is None:
+    if x_tiled is None and want_tiles:
         x_tiled = torch.empty((plan.batch, plan.total_tiles, 64 * plan.head_dim), dtype=x.dtype, device=dev)
     if want_mask and valid_mask is None:
         valid_mask = torch.empty(plan.total_tiles, dtype=torch.int64, device=dev)
@@ -341,13 +346,21 @@ def veda_tile_score_select(plan: Plan, phi_q: Mlp, phi_k: Mlp, scale: float, k_p
 
 def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_ptr, col_idx,
                          softmax_scale: float, out: Optional[torch.Tensor] = None,
-                         lse: Optional[torch.Tensor] = None, want_lse: bool = False):
-    """Stage 4.  Returns (out [batch, heads, N, d] in token order, lse or None)."""
-    dev = q_tiled.device
+                         lse: Optional[torch.Tensor] = None, want_lse: bool = False,
+                         q_tokens: Optional[torch.Tensor] = None):
+    """Stage 4.  Returns (out [batch, heads, N, d] in token order, lse or None).
+    q_tokens (with q_tiled None): Q in token order [batch, heads, N, d], gathered by the kernel."""
+    dev = k_tiled.device
     if out is None:
         out = torch.empty((plan.batch, plan.heads, plan.tokens, plan.head_dim), dtype=plan.dtype, device=dev)
     if want_lse and lse is None:
         lse = torch.empty((plan.batch, plan.heads, plan.tokens), dtype=torch.float32, device=dev)
+    if q_tokens is not None and q_tiled is None:
+        _check(load().veda_sparse_attn_fwd_q_tokens(plan.handle, _ptr(q_tokens), _strides(q_tokens), _ptr(k_tiled),
+                                                    _ptr(v_tiled), _ptr(valid_mask), _ptr(row_ptr), _ptr(col_idx),
+                                                    C.c_float(softmax_scale), _ptr(out), _strides(out), _ptr(lse),
+                                                    _stream()), "veda_sparse_attn_fwd_q_tokens")
+        return out, lse
     _check(load().veda_sparse_attn_fwd(plan.handle, _ptr(q_tiled), _ptr(k_tiled), _ptr(v_tiled),
                                        _ptr(valid_mask), _ptr(row_ptr), _ptr(col_idx), C.c_float(softmax_scale),
                                        _ptr(out), _strides(out), _ptr(lse), _stream()), "veda_sparse_attn_fwd")

@@ -450,6 +450,46 @@ def test_whole_path_wrapper_routes_agree():
         assert torch.equal(o, outs[0][0]) and torch.equal(ci, outs[0][1])
 
 
+@pytest.mark.parametrize("d,tile_tokens", [(128, 64), (64, 64), (128, 128)])
+def test_attention_with_q_in_token_order(d, tile_tokens):
+    # the attention kernel gathering Q itself (no tiled copy of Q): same bits as with the tiled Q; and
+    # the descriptors-only gather gives the same descriptors and masks as the full one
+    if tile_tokens == 64:
+        wl = wlm.custom_workload(f"qtok_{d}", 3, d, "bf16", (9, 18, 18), True, (25, 100), seed=14, batch=2)
+        shapes = wlm.tile_shapes(wl)
+    else:
+        shapes = np.asarray([(8, 4, 4), (2, 8, 8), (1, 8, 16)], np.int32)
+        wl = wlm.custom_workload(f"qtok128_{d}", 3, d, "bf16", (9, 18, 18), True, (25, 100), seed=14, batch=2)
+    dev = torch.device("cuda:0")
+    q, k, v = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, d, wl.grid, shapes, wl.torch_dtype, tile_tokens=tile_tokens)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, want_mask=False)
+    rng = np.random.default_rng(14)
+    kph = [max(1, n // 4) for n in plan.tiles]
+    cols = [np.sort(rng.choice(n, kk, replace=False)) for _ in range(wl.batch) for n, kk in zip(plan.tiles, kph)
+            for _ in range(n)]
+    col_idx = torch.as_tensor(np.concatenate(cols).astype(np.int32)).to(dev)
+    lens = np.concatenate([[kk] * n for _ in range(wl.batch) for n, kk in zip(plan.tiles, kph)])
+    row_ptr = torch.as_tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+    scale = 1.0 / math.sqrt(d)
+    out1, lse1 = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, row_ptr, col_idx, scale, want_lse=True)
+    # a strided view of Q: the gather must honour the strides
+    qpad = torch.zeros((wl.batch, wl.heads, wl.tokens, d + 8), dtype=q.dtype, device=dev)
+    qpad[..., :d] = q
+    out2, lse2 = veda.veda_sparse_attn_fwd(plan, None, kt, vt, vm, row_ptr, col_idx, scale, want_lse=True,
+                                           q_tokens=qpad[..., :d])
+    torch.cuda.synchronize()
+    assert torch.equal(out1.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse1, lse2)
+    if tile_tokens == 64:
+        _, vm_a, vc_a, z_a = veda.veda_tile_layout_stats(plan, q)
+        none, vm_b, vc_b, z_b = veda.veda_tile_layout_stats(plan, q, want_tiles=False)
+        torch.cuda.synchronize()
+        assert none is None and torch.equal(vm_a, vm_b) and torch.equal(vc_a, vc_b)
+        assert torch.equal(z_a.view(torch.int32), z_b.view(torch.int32)) and torch.equal(vm_a, vm)
+
+
 def test_gpu_argument_errors_launch_nothing():
     wl = wlm.WORKLOADS["tiny"]
     run = hz.run_gpu_path(wl, want_lse=False)
