@@ -50,6 +50,10 @@ def parse():
                     help="write the tiled copy of Q and let the attention kernel read it; default (bf16, 64-token "
                          "tiles, descriptors from the gather): Q's gather only takes descriptors and masks, the "
                          "attention kernel gathers Q rows from token order itself")
+    ap.add_argument("--tiled-k", action="store_true",
+                    help="write the tiled copy of K and let the attention kernel read key tiles from it; default "
+                         "(with the default Q route): K's gather only takes descriptors and the attention kernel "
+                         "gathers every kept key tile's rows from token order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the sparse attention call per step")
     ap.add_argument("--tile-tokens", type=int, default=64, choices=(64, 128),
@@ -191,8 +195,11 @@ def main():
 
     # Q straight from token order: needs the descriptor-taking gather (64-token tiles) and the bf16 kernel
     q_from_tokens = not args.tiled_q and not args.unfused and wl.dtype == "bf16"
+    k_from_tokens = q_from_tokens and not args.tiled_k
     if q_from_tokens:
         bytes_layout -= slots * d * es   # the tiled copy of Q is not written
+    if k_from_tokens:
+        bytes_layout -= slots * d * es   # nor that of K
     bufs = {}
 
     def step(events=None):
@@ -204,7 +211,8 @@ def main():
         else:   # TripPool descriptors taken during the Q and K gathers
             qt, vm, vc, zq = veda.veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"),
                                                          bufs.get("zq"), want_tiles=not q_from_tokens)
-            kt, _, _, zk = veda.veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False)
+            kt, _, _, zk = veda.veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False,
+                                                       want_tiles=not k_from_tokens)
             bufs.update(zq=zq, zk=zk)
         vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, bufs.get("vt"), want_mask=False)
         if ev: ev[1].record()
@@ -228,14 +236,16 @@ def main():
             rp, ci = veda.veda_tile_select(plan, s, kph, bufs.get("rp"), bufs.get("ci"))
         if ev: ev[3].record()
         out, _ = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"),
-                                           q_tokens=q if q_from_tokens else None)
+                                           q_tokens=q if q_from_tokens else None,
+                                           k_tokens=k if k_from_tokens else None)
         if ev: ev[4].record()
         bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)
 
     def attn_only(events=None):
         if events: events[3].record()
         veda.veda_sparse_attn_fwd(plan, bufs["qt"], bufs["kt"], bufs["vt"], bufs["vm"], bufs["rp"], bufs["ci"],
-                                  softmax_scale, bufs["out"], q_tokens=q if q_from_tokens else None)
+                                  softmax_scale, bufs["out"], q_tokens=q if q_from_tokens else None,
+                                  k_tokens=k if k_from_tokens else None)
         if events: events[4].record()
 
     step()
@@ -310,8 +320,10 @@ def main():
         result["stage23_fp32"] = {"flop": chain_flops, "tflops": chain_flops / (t23 * 1e-3) / 1e12,
                                   "frac_of_unpacked_vector_peak": chain_flops / (t23 * 1e-3) / 1e12 / (PEAK_F32_VALU_TFLOPS / 2)}
 
-    if (args.dense or args.heatmap) and bufs.get("qt") is None:   # these side runs read the tiled Q
+    if (args.dense or args.heatmap) and bufs.get("qt") is None:   # these side runs read the tiled Q (and K)
         bufs["qt"] = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR, want_mask=False)[0]
+    if (args.dense or args.heatmap) and bufs.get("kt") is None:
+        bufs["kt"] = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)[0]
 
     if args.dense:
         kd = np.asarray(plan.tiles, np.int32)

@@ -214,6 +214,13 @@ veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan*, const void* q, veda_
                                           const void* v_tiled, const uint64_t* valid_mask,
                                           const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
                                           void* out, veda_strides so, float* lse, void* stream);
+/* And with K from token order as well (k, strides sk; bf16 plans; tokens * sk.n * 2 bytes must stay
+ * below 4 GiB): every kept key tile is gathered row by row on its way into the compute unit, so
+ * only V needs a tiled copy.  Bit-identical results again. */
+veda_status veda_sparse_attn_fwd_qk_tokens(const veda_plan*, const void* q, veda_strides sq, const void* k,
+                                           veda_strides sk, const void* v_tiled, const uint64_t* valid_mask,
+                                           const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
+                                           void* out, veda_strides so, float* lse, void* stream);
 
 /* ---- supervision side: target tile scores of full attention and tile recall ------------- */
 /* veda_tile_heatmap (Sec. 4.1 Eq. 3; Sec. 4.3 "Efficient Ground-Truth Heatmap Generation"):

@@ -108,22 +108,28 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a, float 
 
 namespace veda {
 
-// Shared by the two entry points: q_tiled or (q_tok, sq), not both.
+// Shared by the entry points: q_tiled or (q_tok, sq), k_tiled or (k_tok, sk).
 static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const void* q_tok, veda_strides sq,
-                               const void* k_tiled, const void* v_tiled, const uint64_t* valid_mask,
+                               const void* k_tiled, const void* k_tok, veda_strides sk, const void* v_tiled,
+                               const uint64_t* valid_mask,
                                const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale, void* out,
                                veda_strides so, float* lse, void* stream) {
-    if (!pl || (!q_tiled && !q_tok) || !k_tiled || !v_tiled || !valid_mask || !row_ptr || !col_idx || !out)
+    if (!pl || (!q_tiled && !q_tok) || (!k_tiled && !k_tok) || !v_tiled || !valid_mask || !row_ptr || !col_idx || !out)
         return VEDA_ERR_INVALID_ARG;
     if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return VEDA_ERR_INVALID_ARG;
     const int es = pl->elem_size(), d = pl->prob.head_dim;
     if (so.n < d || so.b < 0 || so.h < 0) return VEDA_ERR_INVALID_ARG;
     if (q_tok && (sq.n < d || sq.b < 0 || sq.h < 0)) return VEDA_ERR_INVALID_ARG;
-    if ((q_tiled && !aligned16(q_tiled)) || !aligned16(k_tiled) || !aligned16(v_tiled) || !aligned16(out) ||
+    if (k_tok && (sk.n < d || sk.b < 0 || sk.h < 0)) return VEDA_ERR_INVALID_ARG;
+    if ((q_tiled && !aligned16(q_tiled)) || (k_tiled && !aligned16(k_tiled)) || !aligned16(v_tiled) || !aligned16(out) ||
         (so.b * es) % 16 || (so.h * es) % 16 || (so.n * es) % 16)
         return VEDA_ERR_UNSUPPORTED;
     if (q_tok && (!aligned16(q_tok) || (sq.b * es) % 16 || (sq.h * es) % 16 || (sq.n * es) % 16 ||
                   pl->prob.dtype != VEDA_BF16))
+        return VEDA_ERR_UNSUPPORTED;
+    // a key row's byte offset from its tile's first token is kept in 32 bits
+    if (k_tok && (!aligned16(k_tok) || (sk.b * es) % 16 || (sk.h * es) % 16 || (sk.n * es) % 16 ||
+                  pl->prob.dtype != VEDA_BF16 || pl->tokens() * sk.n * es >= ((int64_t)1 << 32)))
         return VEDA_ERR_UNSUPPORTED;
     // 128-token tiles: the kernel works on the 64-slot halves (inner plan), the CSR on whole tiles
     const veda_plan* ip = pl->inner ? pl->inner : pl;
@@ -133,6 +139,9 @@ static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const v
     a.q = (const char*)q_tiled; a.k = (const char*)k_tiled; a.v = (const char*)v_tiled;
     a.q_tok = (const char*)q_tok;
     a.sq_b = sq.b * es; a.sq_h = sq.h * es; a.sq_n = sq.n * es;
+    a.k_tok = (const char*)k_tok;
+    a.sk_b = sk.b * es; a.sk_h = sk.h * es; a.sk_n = sk.n * es;
+    a.tile_n0 = ip->d_tile_n0;
     a.valid_mask = valid_mask; a.row_ptr = row_ptr; a.col_idx = col_idx;
     a.out = (char*)out; a.lse = lse;
     a.total_tiles = ip->total_tiles;
@@ -161,8 +170,9 @@ extern "C" veda_status veda_sparse_attn_fwd(const veda_plan* pl, const void* q_t
                                             float softmax_scale, void* out, veda_strides so, float* lse,
                                             void* stream) {
     if (!q_tiled) return VEDA_ERR_INVALID_ARG;
-    return veda::sparse_attn(pl, q_tiled, nullptr, veda_strides{0, 0, 0}, k_tiled, v_tiled, valid_mask, row_ptr,
-                             col_idx, softmax_scale, out, so, lse, stream);
+    if (!k_tiled) return VEDA_ERR_INVALID_ARG;
+    return veda::sparse_attn(pl, q_tiled, nullptr, veda_strides{0, 0, 0}, k_tiled, nullptr, veda_strides{0, 0, 0},
+                             v_tiled, valid_mask, row_ptr, col_idx, softmax_scale, out, so, lse, stream);
 }
 
 extern "C" veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan* pl, const void* q, veda_strides sq,
@@ -170,7 +180,17 @@ extern "C" veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan* pl, const 
                                                      const uint64_t* valid_mask, const int32_t* row_ptr,
                                                      const int32_t* col_idx, float softmax_scale, void* out,
                                                      veda_strides so, float* lse, void* stream) {
-    if (!q) return VEDA_ERR_INVALID_ARG;
-    return veda::sparse_attn(pl, nullptr, q, sq, k_tiled, v_tiled, valid_mask, row_ptr, col_idx, softmax_scale, out,
-                             so, lse, stream);
+    if (!q || !k_tiled) return VEDA_ERR_INVALID_ARG;
+    return veda::sparse_attn(pl, nullptr, q, sq, k_tiled, nullptr, veda_strides{0, 0, 0}, v_tiled, valid_mask, row_ptr,
+                             col_idx, softmax_scale, out, so, lse, stream);
+}
+
+extern "C" veda_status veda_sparse_attn_fwd_qk_tokens(const veda_plan* pl, const void* q, veda_strides sq,
+                                                      const void* k, veda_strides sk, const void* v_tiled,
+                                                      const uint64_t* valid_mask, const int32_t* row_ptr,
+                                                      const int32_t* col_idx, float softmax_scale, void* out,
+                                                      veda_strides so, float* lse, void* stream) {
+    if (!q || !k) return VEDA_ERR_INVALID_ARG;
+    return veda::sparse_attn(pl, nullptr, q, sq, nullptr, k, sk, v_tiled, valid_mask, row_ptr, col_idx, softmax_scale,
+                             out, so, lse, stream);
 }

@@ -19,7 +19,10 @@ struct AttnArgs {
     const char* q;             // tiled Q, or null when q_tok is given
     const char* q_tok;         // Q in token order (bf16 kernel only): gathered by the kernel itself
     int64_t sq_b, sq_h, sq_n;  // its strides in bytes
-    const char* k;
+    const char* k;             // tiled K, or null when k_tok is given
+    const char* k_tok;         // K in token order (bf16 kernel only): key tiles gathered row by row
+    int64_t sk_b, sk_h, sk_n;  // its strides in bytes
+    const int32_t* tile_n0;    // token index of slot 0 of every tile (plan table)
     const char* v;
     const uint64_t* valid_mask;
     const int32_t* row_ptr;

@@ -240,12 +240,16 @@ struct MergedStep {
     int j;         // key tile (head-local)
     int fl;        // bit 0: tile A keeps it, bit 1: tile B keeps it; 0 = past the end
     uint64_t vm;   // validity mask of key tile j
+    int n0;        // K from token order: token index of its slot 0
 };
 
 // kGrouped: 128-token tiles.  The geometry in `a` is that of the 64-slot halves (tiles 2o, 2o+1
 // of whole tile o): the workgroup's pair IS one whole query tile, both halves keep the same list
 // (the CSR rows and entries count whole tiles), and every entry expands to its two halves.
-template <int D, bool kGrouped>
+// kTokK: K is read from token order (a.k_tok) instead of the tiled tensor: a key tile's rows
+// are found at first-token + (lt*H + lh)*W + lw; the rows of padded slots are fetched from slot 0
+// instead (any finite or non-finite value will do: their logits are overwritten with -inf).
+template <int D, bool kGrouped, bool kTokK>
 __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs a) {
     constexpr int kRowB = D * 2;                 // bytes of one K row
     constexpr int kKBytes = kTile * kRowB;       // K tile
@@ -282,8 +286,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     const const_i32_t colsB = (const_i32_t)(uintptr_t)(a.col_idx + begB);
     const const_u64_t vmask = (const_u64_t)(uintptr_t)(a.valid_mask + hg.tile_off);
     const int64_t head_tile0 = b * a.total_tiles + hg.tile_off;
-    const char* kt = a.k + head_tile0 * kKBytes;
+    const char* kt = kTokK ? a.k_tok + b * a.sk_b + head * a.sk_h : a.k + head_tile0 * kKBytes;
     const char* vt = a.v + head_tile0 * kVBytes;
+    const const_i32_t n0s = (const_i32_t)(uintptr_t)(a.tile_n0 + hg.tile_off);
 
     // Q operand (B matrix of S^T = K Q^T): lane holds query row 32r+lq, channels 16t+8hh..+8.
     PairState<D> st;
@@ -320,22 +325,39 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     // its fixed LDS position.  Wave w issues instructions w*kLoads .. w*kLoads+kLoads-1 of each
     // tile.
     uint32_t k_src[kLoads], v_src[kLoads];
+    uint32_t k_src0[kLoads];   // kTokK: the same chunk of the tile's slot 0
+    int k_row[kLoads];
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
         const int inst = wave * kLoads + j;
         const int krow = inst * (1024 / kRowB) + lane / kKChunks, kpos = lane % kKChunks;
-        k_src[j] = krow * kRowB + ((kpos ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
+        const uint32_t chunk = (uint32_t)((kpos ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
+        k_row[j] = krow;
+        k_src0[j] = chunk;
+        if (kTokK) {   // byte offset of the row's token from the tile's first token (host checked: fits 32 bits)
+            const int lw = krow % hg.pw, lh = (krow / hg.pw) % hg.ph, lt = krow / (hg.pw * hg.ph);
+            k_src[j] = (uint32_t)((((int64_t)lt * a.H + lh) * a.W + lw) * a.sk_n) + chunk;
+        } else {
+            k_src[j] = krow * kRowB + chunk;
+        }
         const int vrow = inst * 8 + (lane >> 3), vpos = lane & 7;
         v_src[j] = vrow * 128 + ((vpos ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
     }
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t wave_lds = smem_base + (uint32_t)wave * (kLoads * 1024);
-#define VEDA_LOAD_KV(j_tile, SLOT)                                                                         \
+#define VEDA_LOAD_KV(E, SLOT)                                                                              \
     do {                                                                                                   \
-        const char* ksrc_ = kt + (int64_t)(j_tile) * kKBytes;                                              \
-        const char* vsrc_ = vt + (int64_t)(j_tile) * kVBytes;                                              \
-        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
-            dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_, k_src[j]);                           \
+        const int j_tile = (E).j;                                                                          \
+        const char* ksrc_ = kTokK ? kt + (int64_t)(E).n0 * a.sk_n : kt + (int64_t)j_tile * kKBytes;        \
+        const char* vsrc_ = vt + (int64_t)j_tile * kVBytes;                                                \
+        if (kTokK && (E).vm != ~0ull) {   /* edge tile: padded rows have no token */                       \
+            _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                             \
+                dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_,                                  \
+                             ((E).vm >> k_row[j]) & 1ull ? k_src[j] : k_src0[j]);                          \
+        } else {                                                                                           \
+            _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                             \
+                dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_, k_src[j]);                       \
+        }                                                                                                  \
         _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
             dma16_to_lds(wave_lds + (SLOT) * kSlot + kKBytes + j * 1024, vsrc_, v_src[j]);                 \
     } while (0)
@@ -367,6 +389,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
             (e).j = okA ? 2 * rawA + gh : 0;                                         \
             (e).fl = okA ? 3 : 0;                                                    \
             (e).vm = vmask[(e).j];                                                   \
+            (e).n0 = kTokK ? n0s[(e).j] : 0;                                         \
             ia += gh;                                                                \
             gh ^= 1;                                                                 \
             okA = ia < nA;                                                           \
@@ -380,6 +403,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
             (e).j = live_ ? j_ : 0;                                                  \
             (e).fl = ta_ | (tb_ << 1);                                               \
             (e).vm = vmask[(e).j];                                                   \
+            (e).n0 = kTokK ? n0s[(e).j] : 0;                                         \
             ia += ta_;                                                               \
             ib += tb_;                                                               \
             okA = ia < nA;                                                           \
@@ -394,12 +418,12 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     MergedStep e0, e1;
     VEDA_NEXT_STEP(e0);
     VEDA_NEXT_STEP(e1);
-    if (e0.fl) VEDA_LOAD_KV(e0.j, 0);
+    if (e0.fl) VEDA_LOAD_KV(e0, 0);
     VEDA_LOADS_DONE_BARRIER();   // also the Q loads: nothing vector-memory is pending below
 
 #define VEDA_STEP(P)                                                                                     \
     do {                                                                                                 \
-        if (e1.fl) VEDA_LOAD_KV(e1.j, (P) ^ 1);                                                          \
+        if (e1.fl) VEDA_LOAD_KV(e1, (P) ^ 1);                                                            \
         MergedStep e2;                                                                                   \
         VEDA_NEXT_STEP(e2);                                                                              \
         if (e0.fl & my_bit) pair_step<D>(st, fa, e0.vm, (uint32_t)((P) * kSlot));                        \
@@ -423,13 +447,20 @@ veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a,
     const int d = pl->prob.head_dim;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
     const size_t smem = (size_t)2 * 2 * kTile * d * 2;   // two slots of (K tile + V^T tile)
-    if (grouped) {
-        if (d == 128) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<128, true>), grid, block, smem, s, a);
-        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<64, true>), grid, block, smem, s, a);
-    } else {
-        if (d == 128) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<128, false>), grid, block, smem, s, a);
-        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<64, false>), grid, block, smem, s, a);
+#define VEDA_LAUNCH_PAIR(DD, GG, KK) \
+    hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK>), grid, block, smem, s, a)
+    const int variant = (d == 128 ? 4 : 0) | (grouped ? 2 : 0) | (a.k_tok ? 1 : 0);
+    switch (variant) {
+        case 0: VEDA_LAUNCH_PAIR(64, false, false); break;
+        case 1: VEDA_LAUNCH_PAIR(64, false, true); break;
+        case 2: VEDA_LAUNCH_PAIR(64, true, false); break;
+        case 3: VEDA_LAUNCH_PAIR(64, true, true); break;
+        case 4: VEDA_LAUNCH_PAIR(128, false, false); break;
+        case 5: VEDA_LAUNCH_PAIR(128, false, true); break;
+        case 6: VEDA_LAUNCH_PAIR(128, true, false); break;
+        default: VEDA_LAUNCH_PAIR(128, true, true); break;
     }
+#undef VEDA_LAUNCH_PAIR
     return launch_status("sparse_attn_bf16_pair_kernel");
 }
 

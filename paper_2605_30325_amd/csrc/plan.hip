@@ -105,6 +105,19 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     for (int h = 0; h < p->heads; ++h)
         for (int32_t i = 0; i < pl->heads[h].n_tiles; ++i) tile_head[(size_t)pl->heads[h].tile_off + i] = (uint8_t)h;
 
+    // first token of every tile: what a kernel needs to find a tile's rows in token order
+    std::vector<int32_t> tile_n0((size_t)toff);
+    for (int h = 0; h < p->heads; ++h) {
+        const HeadGeom& g = pl->heads[h];
+        for (int32_t i = 0; i < g.n_tiles; ++i) {
+            const int o = g.grp == 2 ? i >> 1 : i, half = g.grp == 2 ? (i & 1) : 0;
+            const int tw = o % g.nw, th = (o / g.nw) % g.nh, tt = o / (g.nw * g.nh);
+            const int64_t t = (int64_t)tt * g.ot + half * g.ht, hh = (int64_t)th * g.oh + half * g.hh,
+                          w = (int64_t)tw * g.ow + half * g.hw;
+            tile_n0[(size_t)g.tile_off + i] = (int32_t)((t * p->H + hh) * p->W + w);
+        }
+    }
+
     std::vector<int32_t> row_blk;
     for (int h = 0; h < p->heads; ++h)
         for (int32_t i = 0; i < (pl->heads[h].n_tiles + 63) / 64; ++i) row_blk.push_back((int32_t)((uint32_t)h << 24 | (uint32_t)i));
@@ -131,6 +144,9 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     hipError_t e = hipGetDevice(&pl->device);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
+    if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_n0, tile_n0.size() * sizeof(int32_t));
+    if (e == hipSuccess)
+        e = hipMemcpy(pl->d_tile_n0, tile_n0.data(), tile_n0.size() * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum, xcd_cum.size() * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_row_blk, row_blk.size() * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_xcd_cum_pair, xcd_cum_pair.size() * sizeof(int32_t));
@@ -187,6 +203,7 @@ void veda_plan_destroy(veda_plan* pl) {
     veda_plan_destroy(pl->inner);
     if (pl->d_heads) (void)hipFree(pl->d_heads);
     if (pl->d_tile_head) (void)hipFree(pl->d_tile_head);
+    if (pl->d_tile_n0) (void)hipFree(pl->d_tile_n0);
     if (pl->d_xcd_cum) (void)hipFree(pl->d_xcd_cum);
     if (pl->d_row_blk) (void)hipFree(pl->d_row_blk);
     if (pl->d_xcd_cum_pair) (void)hipFree(pl->d_xcd_cum_pair);

@@ -92,6 +92,7 @@ struct veda_plan {
     veda_plan* inner = nullptr;
     veda::HeadGeom* d_heads = nullptr;  // device [heads]
     uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
+    int32_t* d_tile_n0 = nullptr;       // device [total_tiles]: token index of slot 0 of each tile (always real)
     // Blocks of 64 consecutive tiles that never straddle two heads (the projection kernel's work
     // items): d_row_blk[x] = head << 24 | block index inside the head.
     int32_t* d_row_blk = nullptr;       // device [row_blocks]

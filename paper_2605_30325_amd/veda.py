@@ -28,7 +28,7 @@ EXPORTS = (
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
     "veda_tile_score_select", "veda_tile_score_select_stats", "veda_sparse_attn_fwd", "veda_sparse_attn_fwd_q_tokens",
-    "veda_tile_heatmap",
+    "veda_sparse_attn_fwd_qk_tokens", "veda_tile_heatmap",
     "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
 
@@ -107,6 +107,9 @@ def load():
     L.veda_sparse_attn_fwd_q_tokens.argtypes = [vp, vp, veda_strides, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides,
                                                 vp, vp]
     L.veda_sparse_attn_fwd_q_tokens.restype = C.c_int
+    L.veda_sparse_attn_fwd_qk_tokens.argtypes = [vp, vp, veda_strides, vp, veda_strides, vp, vp, vp, vp, C.c_float, vp,
+                                                 veda_strides, vp, vp]
+    L.veda_sparse_attn_fwd_qk_tokens.restype = C.c_int
     L.veda_tile_heatmap.argtypes = [vp, vp, vp, vp, C.c_float, vp, i64, vp, vp]
     L.veda_tile_heatmap.restype = C.c_int
     L.veda_tile_recall.argtypes = [vp, C.POINTER(i32), vp, vp, vp, vp, C.c_size_t, vp]
@@ -347,14 +350,22 @@ def veda_tile_score_select(plan: Plan, phi_q: Mlp, phi_k: Mlp, scale: float, k_p
 def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_ptr, col_idx,
                          softmax_scale: float, out: Optional[torch.Tensor] = None,
                          lse: Optional[torch.Tensor] = None, want_lse: bool = False,
-                         q_tokens: Optional[torch.Tensor] = None):
+                         q_tokens: Optional[torch.Tensor] = None, k_tokens: Optional[torch.Tensor] = None):
     """Stage 4.  Returns (out [batch, heads, N, d] in token order, lse or None).
-    q_tokens (with q_tiled None): Q in token order [batch, heads, N, d], gathered by the kernel."""
-    dev = k_tiled.device
+    q_tokens (with q_tiled None): Q in token order [batch, heads, N, d], gathered by the kernel;
+    k_tokens (with q_tokens, k_tiled None): K in token order as well."""
+    dev = v_tiled.device
     if out is None:
         out = torch.empty((plan.batch, plan.heads, plan.tokens, plan.head_dim), dtype=plan.dtype, device=dev)
     if want_lse and lse is None:
         lse = torch.empty((plan.batch, plan.heads, plan.tokens), dtype=torch.float32, device=dev)
+    if q_tokens is not None and k_tokens is not None and q_tiled is None and k_tiled is None:
+        _check(load().veda_sparse_attn_fwd_qk_tokens(plan.handle, _ptr(q_tokens), _strides(q_tokens), _ptr(k_tokens),
+                                                     _strides(k_tokens), _ptr(v_tiled), _ptr(valid_mask),
+                                                     _ptr(row_ptr), _ptr(col_idx), C.c_float(softmax_scale), _ptr(out),
+                                                     _strides(out), _ptr(lse), _stream()),
+               "veda_sparse_attn_fwd_qk_tokens")
+        return out, lse
     if q_tokens is not None and q_tiled is None:
         _check(load().veda_sparse_attn_fwd_q_tokens(plan.handle, _ptr(q_tokens), _strides(q_tokens), _ptr(k_tiled),
                                                     _ptr(v_tiled), _ptr(valid_mask), _ptr(row_ptr), _ptr(col_idx),

@@ -85,6 +85,8 @@ def test_stage_calls_reject_null_plan(lib):
     assert lib.veda_tile_layout_stats(None, None, s, None, None, None, None, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_sparse_attn_fwd_q_tokens(None, None, s, None, None, None, None, None, 0.125, None, s, None,
                                              None) == veda.VEDA_ERR_INVALID_ARG
+    assert lib.veda_sparse_attn_fwd_qk_tokens(None, None, s, None, s, None, None, None, None, 0.125, None, s, None,
+                                              None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_score_stats(None, None, None, None, None, 0.125, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_score_closed_form(None, None, None, None, 0.5, None, None, 0, None) == veda.VEDA_ERR_INVALID_ARG
     assert lib.veda_tile_score_select(None, None, None, None, None, None, 0.125, None, None, None, None, 0,

@@ -480,8 +480,16 @@ def test_attention_with_q_in_token_order(d, tile_tokens):
     qpad[..., :d] = q
     out2, lse2 = veda.veda_sparse_attn_fwd(plan, None, kt, vt, vm, row_ptr, col_idx, scale, want_lse=True,
                                            q_tokens=qpad[..., :d])
+    # K from token order too, again through a strided view; the padded output starts as NaN so that a
+    # real token left unwritten shows
+    kpad = torch.zeros((wl.batch, wl.heads, wl.tokens, d + 8), dtype=k.dtype, device=dev)
+    kpad[..., :d] = k
+    out3 = torch.full_like(out1, float("nan"))
+    out3, lse3 = veda.veda_sparse_attn_fwd(plan, None, None, vt, vm, row_ptr, col_idx, scale, out=out3, want_lse=True,
+                                           q_tokens=qpad[..., :d], k_tokens=kpad[..., :d])
     torch.cuda.synchronize()
     assert torch.equal(out1.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse1, lse2)
+    assert torch.equal(out1.view(torch.int16), out3.view(torch.int16)) and torch.equal(lse1, lse3)
     if tile_tokens == 64:
         _, vm_a, vc_a, z_a = veda.veda_tile_layout_stats(plan, q)
         none, vm_b, vc_b, z_b = veda.veda_tile_layout_stats(plan, q, want_tiles=False)
