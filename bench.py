@@ -31,7 +31,7 @@ PEAK_HBM_GBPS = 8000.0
 # Bytes per sparse-attention launch crossing the L2 -> memory-fabric port, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size
 # (profiles/sparse_attn_waver12b_720p_241f_pmc.txt), keyed by workload; None where not measured.
-MEASURED_TRAFFIC_BYTES = {"waver12b_720p_241f": 2.0 * 90701079 * 1024 + 1317600 * 1024}
+MEASURED_TRAFFIC_BYTES = {"waver12b_720p_241f": 2.0 * 85323922 * 1024 + 1317600 * 1024}
 
 
 def parse():
