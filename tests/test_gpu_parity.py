@@ -526,6 +526,26 @@ def test_outputs_are_deterministic():
     assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
 
 
+def _default_route_matches(run):
+    """The route bench.py times by default (descriptors from stats-only gathers of Q and K, stages 2+3 in
+    one call, attention gathering Q and K rows from token order, only V tiled) against the stage-by-stage
+    run that the oracle checks: same lists, same output bits."""
+    wl, plan = run.wl, run.plan
+    dev = run.q.device
+    pq = veda.Mlp(run.phi_q.w1, run.phi_q.b1, run.phi_q.w2, run.phi_q.b2, run.phi_q.relu, dev)
+    pk = veda.Mlp(run.phi_k.w1, run.phi_k.b1, run.phi_k.w2, run.phi_k.b2, run.phi_k.relu, dev)
+    none_q, vm, _, zq = veda.veda_tile_layout_stats(plan, run.q, want_tiles=False)
+    none_k, _, _, zk = veda.veda_tile_layout_stats(plan, run.k, want_mask=False, want_tiles=False)
+    assert none_q is None and none_k is None and torch.equal(vm, run.bufs["vm"])
+    rp, ci, _ = veda.veda_tile_score_select(plan, pq, pk, run.score_scale, run.k_per_head, stats_q=zq, stats_k=zk)
+    out = torch.full_like(run.out, float("nan"))
+    out, _ = veda.veda_sparse_attn_fwd(plan, None, None, run.bufs["vt"], vm, rp, ci, run.softmax_scale, out=out,
+                                       q_tokens=run.q, k_tokens=run.k)
+    torch.cuda.synchronize()
+    assert torch.equal(rp, run.bufs["rp"]) and torch.equal(ci, run.bufs["ci"]), "kept lists differ"
+    assert torch.equal(out.view(torch.int16), run.out.view(torch.int16)), "attention output differs"
+
+
 def test_wan1p3b_480p_sampled():
     wl = wlm.WORKLOADS["wan1p3b_480p"]
     _say(f"[parity] {wl.name}")
@@ -533,6 +553,7 @@ def test_wan1p3b_480p_sampled():
     assert torch.isfinite(run.out.float()).all()
     for h in (0, 7):
         _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=12)}")
+    _default_route_matches(run)
 
 
 @pytest.mark.parametrize("name", ["wan14b_480p", "wan14b_720p", "waver12b_720p_241f"])
@@ -548,6 +569,8 @@ def test_large_configs_sampled(name):
     # every real token of every head was written (the output buffer starts as NaN)
     for h in range(wl.heads):
         assert torch.isfinite(run.out[0, h].float()).all(), h
+    _say(f"[parity] {wl.name}: the default route of bench.py against this run")
+    _default_route_matches(run)
 
 
 # ---------------------------------------------------------------- supervision side
