@@ -37,8 +37,8 @@ MEASURED_TRAFFIC_BYTES = {"waver12b_720p_241f": 2.0 * 85323922 * 1024 + 1317600 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="waver12b_720p_241f")
     ap.add_argument("--keep", default=None, help="kept fraction NUM/DEN (default: the workload's)")
     ap.add_argument("--dense", action="store_true", help="also time one dense (k = N_T) attention call")
