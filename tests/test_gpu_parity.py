@@ -573,6 +573,37 @@ def test_large_configs_sampled(name):
     _default_route_matches(run)
 
 
+def test_rows_three_times_longer_than_any_named_workload():
+    """783,360 tokens in one head (12,240 tiles per score row): the whole path against the oracle at a 2 %
+    budget (stages 2+3 in one call take the candidate route), then the lists at a 5 % budget (k = 612, where
+    that call falls back to the two stages) against the oracle's selection on the same, already checked, scores."""
+    wl = wlm.custom_workload("long_video", 1, 128, "bf16", (96, 68, 120), False, (2, 100), seed=31)
+    _say(f"[parity] {wl.name}: generating inputs")
+    run = hz.run_gpu_path(wl, want_lse=False)
+    assert run.plan.tiles[0] == 12240 and int(run.k_per_head[0]) == 245
+    _say(f"[parity] {wl.name}: checking against the oracle")
+    _say(f"[parity] {wl.name}: {hz.check_head(run, 0, attn_tiles=4)}")
+    assert torch.isfinite(run.out.float()).all()
+    _default_route_matches(run)
+
+    _say(f"[parity] {wl.name}: 5 % budget")
+    k5 = wlm.keep_budget(wl, (5, 100), run.shapes)
+    assert int(k5[0]) == 612
+    rp2, ci2 = veda.veda_tile_select(run.plan, run.bufs["s"], k5)
+    dev = run.q.device
+    pq = veda.Mlp(run.phi_q.w1, run.phi_q.b1, run.phi_q.w2, run.phi_q.b2, run.phi_q.relu, dev)
+    pk = veda.Mlp(run.phi_k.w1, run.phi_k.b1, run.phi_k.w2, run.phi_k.b2, run.phi_k.relu, dev)
+    rp1, ci1, _ = veda.veda_tile_score_select(run.plan, pq, pk, run.score_scale, k5, q_tiled=run.bufs["qt"],
+                                              k_tiled=run.bufs["kt"], valid_mask=run.bufs["vm"])
+    torch.cuda.synchronize()
+    assert torch.equal(rp1, rp2) and torch.equal(ci1, ci2)
+    rows = hz.sample_tiles(12240, 64, 5)
+    s = run.bufs["s"][0].view(12240, 12240)[torch.as_tensor(rows, device=dev)].cpu().numpy()
+    want = vo.select(s, 612)
+    got = ci2.view(12240, 612)[torch.as_tensor(rows, device=dev)].cpu().numpy()
+    assert np.array_equal(got, want)
+
+
 # ---------------------------------------------------------------- supervision side
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
 def test_target_heatmap_and_recall(dtype, d):
