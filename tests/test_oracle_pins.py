@@ -196,6 +196,33 @@ def test_score_special_cases():
     assert np.array_equal(vo.score(zq, zk, np.float32(0.5)), vo.score(zk, zq, np.float32(0.5)).T)
 
 
+def test_fp32_chains_run_in_ascending_index_order():
+    """The fp32 chains decide the top-k set, so their order is part of the definition: ascending index,
+    the projections starting from the bias, the score from +0.  Inputs whose partial sums absorb a small
+    term make the order visible: (1, 2^30, -2^30) summed left to right gives 0, right to left 1."""
+    big = np.float32(2.0 ** 30)
+    row = np.array([[1.0, big, -big]], np.float32)
+    ones = np.ones((1, 3), np.float32)
+    # score: fma chain from +0 over the latent index, then one multiply by the scale
+    assert vo.score(row, ones, np.float32(0.5))[0, 0] == 0.0
+    assert vo.score(row[:, ::-1].copy(), ones, np.float32(0.5))[0, 0] == 0.5
+    # single layer: chain from the bias; the bias (0.25) is absorbed first, the trailing 1 survives
+    w = np.ones((3, 1), np.float32)
+    quarter = np.array([0.25], np.float32)
+    assert vo.mlp(row, w, quarter)[0, 0] == 0.0                 # ((0.25 + 1) + 2^30) - 2^30
+    assert vo.mlp(row[:, ::-1].copy(), w, quarter)[0, 0] == 1.0   # ((0.25 - 2^30) + 2^30) + 1
+    # two layers, identity first layer (no activation): the second chain sees the same three terms
+    eye, z3 = np.eye(3, dtype=np.float32), np.zeros(3, np.float32)
+    assert vo.mlp(row, eye, z3, w, quarter, relu=False)[0, 0] == 0.0
+    assert vo.mlp(row[:, ::-1].copy(), eye, z3, w, quarter, relu=False)[0, 0] == 1.0
+    # first layer of two: hidden unit j sums the inputs in ascending order from its bias
+    w1 = np.ones((3, 2), np.float32)
+    b1 = np.array([0.25, 0.25], np.float32)
+    w2 = np.array([[1.0], [0.0]], np.float32)
+    assert vo.mlp(row, w1, b1, w2, np.zeros(1, np.float32), relu=False)[0, 0] == 0.0
+    assert vo.mlp(row[:, ::-1].copy(), w1, b1, w2, np.zeros(1, np.float32), relu=False)[0, 0] == 1.0
+
+
 # ---------------------------------------------------------------- stage 3: top-k
 @pytest.mark.parametrize("cols,k", [(4, 2), (37, 1), (37, 5), (64, 64), (130, 17)])
 def test_select_brute_force_and_invariants(cols, k):
