@@ -61,6 +61,9 @@ def parse():
                          "(4x4x4 -> 8x4x4, 1x8x8 -> 2x8x8, 16x2x2 -> 32x2x2); same keep fraction")
     ap.add_argument("--heatmap", action="store_true",
                     help="also time the full-attention target tile scores (two dense Q K^T passes) and Recall@k")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (the per-stage times and the "
+                         "roofline then come from eager steps run after the timed region)")
     ap.add_argument("--unfused", action="store_true",
                     help="stage 2 re-reads the tiled Q and K for its descriptors (veda_tile_layout + veda_tile_score) "
                          "instead of taking them during the gathers")
@@ -251,6 +254,12 @@ def main():
     step()
     torch.cuda.synchronize()
     run = attn_only if args.attn_only else step
+    eager = run
+    if args.graph:   # the stage calls only enqueue kernels: one step replayed as a single graph launch
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager()
+        run = lambda events=None: graph.replay()
     for _ in range(args.warmup):
         run()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
@@ -263,6 +272,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     sclk = clock.summary()
+    if args.graph:   # per-stage durations: the same kernels launched eagerly, outside the timed region
+        for i in range(args.steps):
+            eager(evs[i])
+        torch.cuda.synchronize()
     ms_per_step = wall * 1e3 / args.steps
     # event index pairs of the stages; one call for stages 2+3 leaves no event between them
     spans = {"layout": (0, 1), "score": (1, 2), "select": (2, 3), "attn": (3, 4)}
@@ -283,7 +296,7 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
+        "dtype": wl.dtype, "data": "synthetic", "launch": "hip_graph" if args.graph else "eager",
         "config": {"workload": wl.name, "grid": list(wl.grid), "tokens": N, "heads": heads, "head_dim": d,
                    "tile_tokens": B, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
                    "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch)},

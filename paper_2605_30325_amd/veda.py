@@ -425,17 +425,23 @@ def veda_output_sqerr(plan: Plan, a: torch.Tensor, b: torch.Tensor, err: Optiona
 
 def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, score_scale: float,
                    softmax_scale: float, buffers: Optional[dict] = None, fused: bool = False,
-                   one_call: bool = False):
+                   one_call: bool = False, from_tokens: bool = False):
     """The whole path in call order: layout x3 -> score -> select -> sparse attention.
     fused=True takes the descriptors during the Q and K gathers (veda_tile_layout_stats +
     veda_tile_score_stats); one_call=True runs stages 2 and 3 through veda_tile_score_select*,
-    which never writes the score matrix; the results are bit-identical whichever way.
+    which never writes the score matrix; from_tokens=True (with fused, bf16, 64-token tiles) writes no
+    tiled copy of Q and K: the gathers only take descriptors and masks, and the attention kernel
+    gathers the rows of both from token order.  The results are bit-identical whichever way.
     `buffers` (optional dict) is filled on the first call and reused afterwards so that a
     steady-state step allocates nothing."""
     bufs = {} if buffers is None else buffers
+    if from_tokens and not fused:
+        raise ValueError("from_tokens needs fused=True (the descriptors must come from the gathers)")
     if fused:
-        qt, vm, vc, zq = veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"), bufs.get("zq"))
-        kt, _, _, zk = veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False)
+        qt, vm, vc, zq = veda_tile_layout_stats(plan, q, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"), bufs.get("zq"),
+                                                want_tiles=not from_tokens)
+        kt, _, _, zk = veda_tile_layout_stats(plan, k, bufs.get("kt"), stats=bufs.get("zk"), want_mask=False,
+                                              want_tiles=not from_tokens)
         bufs.update(zq=zq, zk=zk)
     else:
         qt, vm, vc = veda_tile_layout(plan, q, VEDA_TOKEN_MAJOR, bufs.get("qt"), bufs.get("vm"), bufs.get("vc"))
@@ -456,6 +462,7 @@ def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, scor
         else:
             s, ws = veda_tile_score(plan, qt, kt, vm, phi_q, phi_k, score_scale, bufs.get("s"), bufs.get("ws"))
         rp, ci = veda_tile_select(plan, s, k_per_head, bufs.get("rp"), bufs.get("ci"))
-    out, _ = veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"))
+    out, _ = veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, bufs.get("out"),
+                                  q_tokens=q if from_tokens else None, k_tokens=k if from_tokens else None)
     bufs.update(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci, out=out)
     return out, bufs

@@ -424,8 +424,9 @@ def test_score_select_in_one_call_other_shapes():
 
 
 def test_whole_path_wrapper_routes_agree():
-    # veda_attention in its four routes (descriptors from the gather or not, stages 2+3 in one call
-    # or two): same lists, same output bits; buffers of a first call are reused by a second
+    # veda_attention in its six routes (descriptors from the gather or not, stages 2+3 in one call
+    # or two, Q and K tiled or read from token order): same lists, same output bits; buffers of a
+    # first call are reused by a second
     wl = wlm.custom_workload("routes", 3, 128, "bf16", (9, 18, 18), True, (25, 100), seed=12)
     dev = torch.device("cuda:0")
     shapes = wlm.tile_shapes(wl)
@@ -436,18 +437,54 @@ def test_whole_path_wrapper_routes_agree():
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
     pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
     outs = []
-    for fused in (False, True):
-        for one_call in (False, True):
-            out, bufs = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
-                                            fused=fused, one_call=one_call)
-            first = out.clone()
-            out2, _ = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
-                                          buffers=bufs, fused=fused, one_call=one_call)
-            torch.cuda.synchronize()
-            assert out2.data_ptr() == out.data_ptr() and torch.equal(out2.view(torch.int16), first.view(torch.int16))
-            outs.append((out2.view(torch.int16).clone(), bufs["ci"].clone()))
+    for fused, one_call, from_tokens in ((False, False, False), (False, True, False), (True, False, False),
+                                         (True, True, False), (True, False, True), (True, True, True)):
+        out, bufs = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
+                                        fused=fused, one_call=one_call, from_tokens=from_tokens)
+        assert (bufs["qt"] is None and bufs["kt"] is None) == from_tokens
+        first = out.clone()
+        out2, _ = veda.veda_attention(plan, q, k, v, pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128),
+                                      buffers=bufs, fused=fused, one_call=one_call, from_tokens=from_tokens)
+        torch.cuda.synchronize()
+        assert out2.data_ptr() == out.data_ptr() and torch.equal(out2.view(torch.int16), first.view(torch.int16))
+        outs.append((out2.view(torch.int16).clone(), bufs["ci"].clone()))
     for o, ci in outs[1:]:
         assert torch.equal(o, outs[0][0]) and torch.equal(ci, outs[0][1])
+
+
+def test_whole_path_replayed_from_a_hip_graph():
+    """The stage calls only enqueue kernels on the caller's stream, so one whole step can be captured into a
+    HIP graph.  Replays with fresh inputs copied into the captured buffers, and unrelated eager work between
+    them, must reproduce the eager results bit for bit every time."""
+    wl = wlm.custom_workload("graph", 3, 128, "bf16", (9, 18, 18), True, (25, 100), seed=14)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    kph = wlm.keep_budget(wl, None, shapes)
+    eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
+    pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
+    pk = veda.Mlp(ek.w1, ek.b1, ek.w2, ek.b2, ek.relu, dev)
+    args = (pq, pk, kph, hz.score_scale_of(wl), 1.0 / math.sqrt(128))
+    kw = dict(fused=True, one_call=True, from_tokens=True)
+    inputs = [wlm.make_qkv(wlm.custom_workload("graph", 3, 128, "bf16", (9, 18, 18), True, (25, 100), seed=14 + i), dev)
+              for i in range(4)]
+    q, k, v = (x.clone() for x in inputs[0])
+    _, bufs = veda.veda_attention(plan, q, k, v, *args, **kw)        # allocates the step's buffers
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        veda.veda_attention(plan, q, k, v, *args, buffers=bufs, **kw)
+    scratch = torch.zeros(1 << 20, device=dev)
+    for rep, (qi, ki, vi) in enumerate(inputs[1:] + inputs[:1]):
+        want, wb = veda.veda_attention(plan, qi, ki, vi, *args, **kw)   # eager, its own buffers
+        want, want_ci = want.view(torch.int16).clone(), wb["ci"].clone()
+        q.copy_(qi); k.copy_(ki); v.copy_(vi)
+        scratch.add_(1.0).mul_(0.5)                                   # eager work between the replays
+        bufs["out"].fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bufs["ci"], want_ci), rep
+        assert torch.equal(bufs["out"].view(torch.int16), want), rep
 
 
 @pytest.mark.parametrize("d,tile_tokens", [(128, 64), (64, 64), (128, 128)])
