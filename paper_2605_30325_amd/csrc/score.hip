@@ -97,12 +97,21 @@ constexpr int kMlpXsFloats = kMlpRows * kMlpXPitch;   // one input stage
 
 // One affine layer for the 64 rows of a workgroup:
 //   out[r][n] = act(bias[n] + sum_k x[r][k] * w[k][n]),  one fmaf chain per (r,n), k ascending.
-// Thread (rg = tid/32, jg = tid%32) keeps rows 8*rg..+7 x outputs c0+4*jg..+3 in registers.  The
-// weights of 16 reduction indices x 128 outputs are staged in LDS per step (ws, two buffers);
+// The chains run on the matrix cores: v_mfma_f32_32x32x2_f32 adds its two products to the
+// accumulator one after the other, each with its own rounding, in ascending k -- measured on
+// gfx950 to give the bits of fmaf(x[k+1], w[k+1], fmaf(x[k], w[k], acc)) on 245,760 random chains
+// of 64 terms, denormal sums and products included -- so a chain of these instructions over
+// k = 0, 2, 4, ... started from the bias IS the chain above, at twice the rate of scalar fp32
+// fma.  Wave w of the four owns output columns c0+32w..+31 for both 32-row halves (two 32x32
+// accumulators); lane (col = lane%32, kh = lane/32) feeds x[row = col (+32)][k+kh] and
+// w[k+kh][column] and holds rows (r%4) + 8(r/4) + 4kh of its column in register r.
+// The weights of 16 reduction indices x 128 outputs are staged in LDS per step (ws, two buffers);
 // the inputs come either from global memory, staged alongside (xs, two buffers), or from a
 // resident LDS array (x_lds).  The global loads of step s+1 are in flight while step s is
 // computed; one barrier per step.  Results go to an LDS array (y_lds, pitch ldy) or to global
 // rows (y_glb, pitch N).
+typedef __attribute__((ext_vector_type(16))) float mlp_f32x16;
+
 template <bool kXGlobal, bool kYLds>
 __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const float* x_lds, int ldx, int rows,
                                           int K, const float* __restrict__ w, const float* __restrict__ bias,
@@ -110,17 +119,15 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
                                           float* xs, float* ws) {
     constexpr int kWPer = kMlpWsFloats / kMlpThreads;   // staged weights per thread and step (8)
     static_assert(kMlpRows * (kMlpK / 4) == kMlpThreads, "one float4 of the inputs per thread and step");
-    const int jg = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    static_assert(kMlpRows == 64 && kMlpCols == 128 && kMlpThreads == 256, "four waves x (2 x 32 rows) x 32 columns");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, kh = lane >> 5;
     const int xr = threadIdx.x / (kMlpK / 4), xi = (threadIdx.x % (kMlpK / 4)) * 4;   // staged input float4
     for (int c0 = 0; c0 < N; c0 += kMlpCols) {
-        float acc[8][4];
+        const int n = c0 + 32 * wave + col;
+        const float bv = n < N ? bias[n] : 0.0f;
+        mlp_f32x16 acc[2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int n = c0 + 4 * jg + e;
-            const float bv = n < N ? bias[n] : 0.0f;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) acc[r][e] = bv;
-        }
+        for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = bv;
         float wreg[kWPer];
         float4 xreg = make_float4(0.f, 0.f, 0.f, 0.f);
         auto fetch = [&](int k0) {
@@ -149,61 +156,53 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
             const int kc = K - k0 < kMlpK ? K - k0 : kMlpK;
             const bool more = k0 + kMlpK < K;
             if (more) fetch(k0 + kMlpK);
-            const float* wb = ws + buf * kMlpWsFloats;
-            const float* xb = kXGlobal ? xs + buf * kMlpXsFloats + (8 * rg) * kMlpXPitch : x_lds + (8 * rg) * ldx + k0;
+            const float* wb = ws + buf * kMlpWsFloats + 32 * wave + col + kh * kMlpCols;
             const int xp = kXGlobal ? kMlpXPitch : ldx;
-            int kk = 0;
-            for (; kk + 4 <= kc; kk += 4) {
-                float4 wv[4];
+            const float* xb = (kXGlobal ? xs + buf * kMlpXsFloats : x_lds + k0) + col * xp + kh;
+            if (kc == kMlpK) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) wv[e] = *reinterpret_cast<const float4*>(wb + (kk + e) * kMlpCols + 4 * jg);
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const float4 xv = *reinterpret_cast<const float4*>(xb + r * xp + kk);
-                    acc[r][0] = __builtin_fmaf(xv.x, wv[0].x, acc[r][0]);
-                    acc[r][1] = __builtin_fmaf(xv.x, wv[0].y, acc[r][1]);
-                    acc[r][2] = __builtin_fmaf(xv.x, wv[0].z, acc[r][2]);
-                    acc[r][3] = __builtin_fmaf(xv.x, wv[0].w, acc[r][3]);
-                    acc[r][0] = __builtin_fmaf(xv.y, wv[1].x, acc[r][0]);
-                    acc[r][1] = __builtin_fmaf(xv.y, wv[1].y, acc[r][1]);
-                    acc[r][2] = __builtin_fmaf(xv.y, wv[1].z, acc[r][2]);
-                    acc[r][3] = __builtin_fmaf(xv.y, wv[1].w, acc[r][3]);
-                    acc[r][0] = __builtin_fmaf(xv.z, wv[2].x, acc[r][0]);
-                    acc[r][1] = __builtin_fmaf(xv.z, wv[2].y, acc[r][1]);
-                    acc[r][2] = __builtin_fmaf(xv.z, wv[2].z, acc[r][2]);
-                    acc[r][3] = __builtin_fmaf(xv.z, wv[2].w, acc[r][3]);
-                    acc[r][0] = __builtin_fmaf(xv.w, wv[3].x, acc[r][0]);
-                    acc[r][1] = __builtin_fmaf(xv.w, wv[3].y, acc[r][1]);
-                    acc[r][2] = __builtin_fmaf(xv.w, wv[3].z, acc[r][2]);
-                    acc[r][3] = __builtin_fmaf(xv.w, wv[3].w, acc[r][3]);
+                for (int kk = 0; kk < kMlpK; kk += 2) {
+                    const float b = wb[kk * kMlpCols];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb[kk], b, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb[32 * xp + kk], b, acc[1], 0, 0, 0);
                 }
-            }
-            for (; kk < kc; ++kk) {   // tail of a reduction length that is not a multiple of 4
-                const float4 wv = *reinterpret_cast<const float4*>(wb + kk * kMlpCols + 4 * jg);
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const float xv = xb[r * xp + kk];
-                    acc[r][0] = __builtin_fmaf(xv, wv.x, acc[r][0]);
-                    acc[r][1] = __builtin_fmaf(xv, wv.y, acc[r][1]);
-                    acc[r][2] = __builtin_fmaf(xv, wv.z, acc[r][2]);
-                    acc[r][3] = __builtin_fmaf(xv, wv.w, acc[r][3]);
+            } else {
+                int kk = 0;
+                for (; kk + 2 <= kc; kk += 2) {
+                    const float b = wb[kk * kMlpCols];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb[kk], b, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb[32 * xp + kk], b, acc[1], 0, 0, 0);
+                }
+                if (kk < kc) {
+                    // odd reduction length: the instruction's second term is made -0 * +0 = -0, the one
+                    // addend that leaves every accumulator value, signed zeros included, as it is
+                    const float b = kh ? 0.0f : wb[kk * kMlpCols];
+                    const float a0 = kh ? -0.0f : xb[kk], a1 = kh ? -0.0f : xb[32 * xp + kk];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b, acc[1], 0, 0, 0);
                 }
             }
             if (more) stash(buf ^ 1);
             __syncthreads();
         }
+        if (n < N) {
+            // one running pointer, advanced store by store: 32 precomputed 64-bit addresses would
+            // not fit beside the accumulators
+            float* yp = kYLds ? y_lds + (4 * kh) * ldy + n : y_glb + (int64_t)(4 * kh) * N + n;
+            const int pitch = kYLds ? ldy : N;
+            int row = 4 * kh;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int row = 8 * rg + r;
+            for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int n = c0 + 4 * jg + e;
-                const float v = (relu && !(acc[r][e] > 0.0f)) ? 0.0f : acc[r][e];
-                if (n < N) {
-                    if (kYLds) y_lds[row * ldy + n] = v;
-                    else if (row < rows) y_glb[(int64_t)row * N + n] = v;
+                for (int r = 0; r < 16; ++r) {
+                    const float v = (relu && !(acc[rb][r] > 0.0f)) ? 0.0f : acc[rb][r];
+                    if (kYLds || row < rows) *yp = v;
+                    // next row: +1 inside a group of four, +5 to the next group (rows 8g..8g+3 of this lane half)
+                    const int step = (r & 3) == 3 ? 5 : 1;
+                    yp += (int64_t)step * pitch;
+                    row += step;
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            }
         }
     }
 }
@@ -211,7 +210,7 @@ __device__ __forceinline__ void mlp_layer(const float* __restrict__ x_glb, const
 // One workgroup projects up to 64 consecutive tiles of one head (Eq. 5, phi_q or phi_k).
 // row_blk[x] = head << 24 | index of the 64-tile block inside that head.
 // grid = (row blocks of all heads, 2 estimators, batch); dynamic LDS = staging + hidden layer.
-__global__ __launch_bounds__(kMlpThreads, 4) void mlp_kernel(const HeadGeom* __restrict__ heads,
+__global__ __launch_bounds__(kMlpThreads, 3) void mlp_kernel(const HeadGeom* __restrict__ heads,
                                                          const int32_t* __restrict__ row_blk,
                                                          const float* __restrict__ zq, const float* __restrict__ zk,
                                                          float* __restrict__ yq, float* __restrict__ yk,
@@ -234,7 +233,7 @@ __global__ __launch_bounds__(kMlpThreads, 4) void mlp_kernel(const HeadGeom* __r
     float* out = y + row0 * p.out_dim;
     if (p.hidden && hglb) {
         // The 64 x hidden intermediate goes through global memory (it stays in L2): without it in
-        // LDS twice as many workgroups fit on a compute unit.  The barrier that opens the second
+        // LDS more workgroups fit on a compute unit (three instead of two).  The barrier that opens the second
         // layer also orders these stores before its loads (same workgroup).
         float* hrow = hglb + row0 * p.hidden;
         mlp_layer<true, false>(x, nullptr, 0, rows, p.in_dim, p.w1 + (int64_t)head * p.in_dim * p.hidden,

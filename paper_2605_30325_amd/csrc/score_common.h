@@ -17,7 +17,7 @@ void launch_trippool(const veda_plan* pl, const void* q_tiled, const void* k_til
 
 // phi_q, phi_k (Eq. 5) of the descriptors into the latents yq, yk ([rows][out_dim] fp32 each).
 // hq, hk: optional scratch of [rows][hidden] floats each for the hidden layers (else they stay
-// in LDS, which halves the workgroups resident per compute unit).
+// in LDS, which leaves room for fewer workgroups per compute unit).
 veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k, const float* zq,
                                const float* zk, float* yq, float* yk, float* hq, float* hk, hipStream_t s);
 
