@@ -257,9 +257,12 @@ constexpr int kSC = 32;       // latent coordinates staged per step
 constexpr int kSPitch = 36;   // LDS pitch of one staged latent row (floats): rows stay 16-byte
                               // aligned and 8 consecutive rows start in 8 different bank groups
 
-// A 128x128 block (bi, bj) of one head's score matrix (Eq. 5) by one workgroup; thread (ti,tj)
-// keeps the 8x8 patch rows ti+16a, columns tj+16e.  Latent rows are staged row-major in LDS,
-// 32 coordinates at a time; every score is one fmaf chain over ascending coordinate from +0.
+// A 128x128 block (bi, bj) of one head's score matrix (Eq. 5) by one workgroup.  Every score is
+// one fma chain over ascending latent coordinate from +0, run on the matrix cores like the
+// projections' (see mlp_layer: v_mfma_f32_32x32x2_f32 over the coordinate pairs gives the bits of
+// the fmaf chain).  Wave w holds rows 32w..32w+31 x all 128 columns in four 32x32 accumulators:
+// register r of lane (col = lane%32, kh = lane/32) is row (r%4) + 8(r/4) + 4kh, column 32cb + col.
+// Latent rows are staged row-major in LDS, 32 coordinates at a time.
 __device__ __forceinline__ void score_block_128(const HeadGeom& hg, int bi, int bj, int64_t b, float* qs, float* ks,
                                                 const float* __restrict__ yq, const float* __restrict__ yk,
                                                 float* __restrict__ scores, int dp, float scale,
@@ -267,12 +270,12 @@ __device__ __forceinline__ void score_block_128(const HeadGeom& hg, int bi, int 
     const int nT = hg.n_tiles;
     const float* qbase = yq + (b * total_tiles + hg.tile_off) * dp;
     const float* kbase = yk + (b * total_tiles + hg.tile_off) * dp;
-    const int ti = threadIdx.x / 16, tj = threadIdx.x % 16;
-    float acc[8][8];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, kh = lane >> 5;
+    mlp_f32x16 acc[4];
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[a][e] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.0f;
     for (int c0 = 0; c0 < dp; c0 += kSC) {
         const int cn = dp - c0 < kSC ? dp - c0 : kSC;   // multiple of 4
         __syncthreads();
@@ -287,40 +290,40 @@ __device__ __forceinline__ void score_block_128(const HeadGeom& hg, int bi, int 
             *reinterpret_cast<float4*>(ks + r * kSPitch + c4) = kv;
         }
         __syncthreads();
-        for (int c = 0; c < cn; c += 4) {
-            float4 kb[8];
+        const float* qa = qs + (32 * wave + col) * kSPitch + kh;   // A: q[row = col][c + kh]
+        const float* kb = ks + col * kSPitch + kh;                  // B: k[column = col][c + kh]
+        if (cn == kSC) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) kb[e] = *reinterpret_cast<const float4*>(ks + (tj + 16 * e) * kSPitch + c);
+            for (int c = 0; c < kSC; c += 2) {
+                const float a = qa[c];
 #pragma unroll
-            for (int a = 0; a < 8; ++a) {
-                const float4 qa = *reinterpret_cast<const float4*>(qs + (ti + 16 * a) * kSPitch + c);
+                for (int cb = 0; cb < 4; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, kb[32 * cb * kSPitch + c], acc[cb], 0, 0, 0);
+            }
+        } else {
+            for (int c = 0; c < cn; c += 2) {
+                const float a = qa[c];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    float v = acc[a][e];
-                    v = __builtin_fmaf(qa.x, kb[e].x, v);
-                    v = __builtin_fmaf(qa.y, kb[e].y, v);
-                    v = __builtin_fmaf(qa.z, kb[e].z, v);
-                    v = __builtin_fmaf(qa.w, kb[e].w, v);
-                    acc[a][e] = v;
-                }
+                for (int cb = 0; cb < 4; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, kb[32 * cb * kSPitch + c], acc[cb], 0, 0, 0);
             }
         }
     }
     float* sbase = scores + b * score_elems + hg.score_off;
 #pragma unroll
-    for (int a = 0; a < 8; ++a) {
-        const int i = bi * kSB + ti + 16 * a;
+    for (int r = 0; r < 16; ++r) {
+        const int i = bi * kSB + 32 * wave + (r & 3) + 8 * (r >> 2) + 4 * kh;
         if (i >= nT) continue;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int j = bj * kSB + tj + 16 * e;
-            if (j < nT) sbase[(int64_t)i * nT + j] = acc[a][e] * scale;
+        for (int cb = 0; cb < 4; ++cb) {
+            const int j = bj * kSB + 32 * cb + col;
+            if (j < nT) sbase[(int64_t)i * nT + j] = acc[cb][r] * scale;
         }
     }
 }
 
 // All score blocks, one workgroup each.
-__global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
+__global__ __launch_bounds__(256, 3) void score_kernel(const HeadGeom* __restrict__ heads, int n_heads,
                                                     const float* __restrict__ yq, const float* __restrict__ yk,
                                                     float* __restrict__ scores, int dp, float scale,
                                                     int64_t total_tiles, int64_t score_elems) {
@@ -341,7 +344,7 @@ __global__ __launch_bounds__(256) void score_kernel(const HeadGeom* __restrict__
 // entries of the 64-row table), which leaves at once unless one of the marks of its rows is set
 // (marks: one per 128 consecutive rows of the latents, row >> 7) and otherwise forms all the
 // blocks of its rows.
-__global__ __launch_bounds__(256) void score_marked_rows_kernel(const HeadGeom* __restrict__ heads,
+__global__ __launch_bounds__(256, 2) void score_marked_rows_kernel(const HeadGeom* __restrict__ heads,
                                                                 const int32_t* __restrict__ row_blk,
                                                                 const float* __restrict__ yq,
                                                                 const float* __restrict__ yk,
