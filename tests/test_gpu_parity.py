@@ -101,6 +101,32 @@ def test_estimator_shapes_bit_exact(hidden, dp, relu):
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"{wl.name} head {h}: scores not bit-exact"
 
 
+def test_projection_chains_of_odd_length_keep_signed_zeros():
+    """Hidden width 5: the second layer's chains have an odd number of terms, so the last matrix-core
+    instruction of each chain carries a padding term, which must leave a -0 accumulator as -0
+    (bias -0, every product 1 * -0): the latents are -0 in the oracle and on the GPU."""
+    wl = wlm.custom_workload("negzero", 1, 64, "f32", (4, 8, 8), False, (1, 2), seed=5, latent_dim=4)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    w1 = np.zeros((1, 192, 5), np.float32)
+    b1 = np.ones((1, 5), np.float32)
+    w2 = np.full((1, 5, 4), -0.0, np.float32)
+    b2 = np.full((1, 4), -0.0, np.float32)
+    z = vo.trippool(hz.to_f32_numpy(q[0, 0]), wl.grid, (4, 4, 4))
+    want = vo.mlp(z, w1[0], b1[0], w2[0], b2[0], True)
+    assert np.all(want.view(np.uint32) == 0x80000000)
+    phi = veda.Mlp(w1, b1, w2, b2, True, dev)
+    _, ws = veda.veda_tile_score(plan, qt, kt, vm, phi, phi, 0.5)
+    torch.cuda.synchronize()
+    rows, d, dp = plan.total_tiles, 64, 4
+    y = ws.view(torch.float32)[2 * rows * 3 * d: 2 * rows * 3 * d + 2 * rows * dp].cpu().numpy()
+    assert np.all(y.view(np.uint32) == 0x80000000)
+
+
 def test_zero_sparsity_equals_dense_attention_on_gpu():
     wl = wlm.custom_workload("dense_identity", 3, 128, "bf16", (6, 9, 11), True, (1, 1), seed=13)
     run = hz.run_gpu_path(wl)
