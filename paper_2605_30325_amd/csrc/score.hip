@@ -3,7 +3,9 @@
 //
 // The scores decide an integer (the top-k set), so every number here is produced by a fixed
 // sequence of IEEE fp32 operations: this file is compiled with floating-point contraction
-// off, every fused multiply-add is written as fmaf, and no chain is split or re-associated.
+// off, every fused multiply-add is written as fmaf or issued as v_mfma_f32_32x32x2_f32 (which
+// applies its two terms one after the other as fmas: see mlp_layer), and no chain is split or
+// re-associated.
 //   TripPool : sum over real slots in ascending slot order from +0; avg = sum * (1/count)
 //              with 1/count rounded once on the host; max/min by plain comparisons.
 //   phi      : per output, one fmaf chain over ascending input index started from the bias.
