@@ -127,6 +127,51 @@ def test_projection_chains_of_odd_length_keep_signed_zeros():
     assert np.all(y.view(np.uint32) == 0x80000000)
 
 
+def test_projection_and_score_chains_in_the_denormal_range():
+    """Weights of magnitude 2^-136 (denormal themselves): every product and partial sum of the projection
+    chains is a denormal number, and so are the latents; the scores underflow.  Nothing may be flushed to
+    zero on the way: latents and scores have the oracle's bits (two layers and a single one)."""
+    wl = wlm.custom_workload("denormal", 1, 64, "f32", (4, 8, 8), False, (1, 2), seed=6, latent_dim=8)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    q, k, _ = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
+    kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
+    rng = np.random.default_rng(8)
+    tiny = np.float32(2.0 ** -136)
+    rows, d, dp = plan.total_tiles, 64, 8
+    zq = vo.trippool(hz.to_f32_numpy(q[0, 0]), wl.grid, (4, 4, 4))
+    zk = vo.trippool(hz.to_f32_numpy(k[0, 0]), wl.grid, (4, 4, 4))
+    for hidden in (0, 12):
+        first = hidden if hidden else dp
+        w1 = (rng.uniform(-1, 1, (1, 3 * d, first)).astype(np.float32) * (tiny if not hidden else np.float32(1.0)))
+        b1 = np.zeros((1, first), np.float32)
+        w2 = rng.uniform(-1, 1, (1, hidden, dp)).astype(np.float32) * tiny if hidden else None
+        b2 = rng.uniform(-1, 1, (1, dp)).astype(np.float32) * tiny if hidden else None
+        args = (w1[0], b1[0], None if w2 is None else w2[0], None if b2 is None else b2[0], False)
+        want_q, want_k = vo.mlp(zq, *args), vo.mlp(zk, *args)
+        assert np.all(np.abs(want_q[want_q != 0]) < 1.1754944e-38) and np.count_nonzero(want_q) > want_q.size // 2
+        phi = veda.Mlp(w1, b1, w2, b2, False, dev)
+        s, ws = veda.veda_tile_score(plan, qt, kt, vm, phi, phi, 1.0)
+        torch.cuda.synchronize()
+        y = ws.view(torch.float32)[2 * rows * 3 * d: 2 * rows * 3 * d + 2 * rows * dp].cpu().numpy()
+        assert np.array_equal(y[: rows * dp].view(np.uint32), want_q.ravel().view(np.uint32)), hidden
+        assert np.array_equal(y[rows * dp:].view(np.uint32), want_k.ravel().view(np.uint32)), hidden
+        ref = vo.score(want_q, want_k, np.float32(1.0))
+        assert np.array_equal(s[0].view(rows, rows).cpu().numpy().view(np.uint32), ref.view(np.uint32)), hidden
+    # scores in the denormal range too: latents of magnitude 2^-68 give products near 2^-136
+    w1 = rng.uniform(-1, 1, (1, 3 * d, dp)).astype(np.float32) * np.float32(2.0 ** -72)
+    b1 = np.zeros((1, dp), np.float32)
+    yq, yk = vo.mlp(zq, w1[0], b1[0], None, None, False), vo.mlp(zk, w1[0], b1[0], None, None, False)
+    ref = vo.score(yq, yk, np.float32(1.0))
+    assert np.count_nonzero(ref) > ref.size // 2 and np.all(np.abs(ref) < 1.1754944e-38)
+    phi = veda.Mlp(w1, b1, None, None, False, dev)
+    s, _ = veda.veda_tile_score(plan, qt, kt, vm, phi, phi, 1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(s[0].view(rows, rows).cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 def test_zero_sparsity_equals_dense_attention_on_gpu():
     wl = wlm.custom_workload("dense_identity", 3, 128, "bf16", (6, 9, 11), True, (1, 1), seed=13)
     run = hz.run_gpu_path(wl)
