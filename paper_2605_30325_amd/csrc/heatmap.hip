@@ -178,7 +178,9 @@ __global__ __launch_bounds__(256) void tile_heatmap_bf16_kernel(HeatArgs a) {
             f32x16 s[2];
             heat_logits<D>(s, qf, k0 + (uint32_t)((j & 1) * kKBytes), vm, hh);
             // softmax_scale > 0: the largest logit is the largest dot product, scaled
-            const float m_new = fmaxf(m, heat_row_max(s) * a.scale_log2);   // finite: every tile has a real slot
+            // finite from j = 0 on: tile 0 starts at the grid origin (a later half tile of a ragged
+            // grid may be all padding: its logits are -inf and add nothing)
+            const float m_new = fmaxf(m, heat_row_max(s) * a.scale_log2);
             float psum = 0.0f;
 #pragma unroll
             for (int c = 0; c < 2; ++c)

@@ -47,20 +47,8 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     int64_t toff = 0, soff = 0, boff = 0;
     for (int h = 0; h < p->heads; ++h) {
         HeadGeom& g = pl->heads[h];
-        g.ot = pl->shapes[3 * h]; g.oh = pl->shapes[3 * h + 1]; g.ow = pl->shapes[3 * h + 2];
-        g.pt = g.ot; g.ph = g.oh; g.pw = g.ow;
-        g.ht = g.hh = g.hw = 0;
-        g.grp = grp;
-        if (grp == 2) {   // cut across the slowest axis of extent > 1 (a product of 128: it is even)
-            if (g.ot > 1) { g.pt = g.ot / 2; g.ht = g.pt; }
-            else if (g.oh > 1) { g.ph = g.oh / 2; g.hh = g.ph; }
-            else { g.pw = g.ow / 2; g.hw = g.pw; }
-        }
-        g.nt = (p->T + g.ot - 1) / g.ot;
-        g.nh = (p->H + g.oh - 1) / g.oh;
-        g.nw = (p->W + g.ow - 1) / g.ow;
-        const int64_t n = (int64_t)grp * g.nt * g.nh * g.nw;
-        g.n_tiles = (int32_t)n;
+        veda::head_extents(g, &pl->shapes[3 * h], grp, p->T, p->H, p->W);
+        const int64_t n = g.n_tiles;
         if (grp == 2) {
             g.pair_ax = 3;
             g.n_pairs = (int32_t)(n / 2);
@@ -105,16 +93,18 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     for (int h = 0; h < p->heads; ++h)
         for (int32_t i = 0; i < pl->heads[h].n_tiles; ++i) tile_head[(size_t)pl->heads[h].tile_off + i] = (uint8_t)h;
 
-    // first token of every tile: what a kernel needs to find a tile's rows in token order
+    // anchor token of every tile: what a kernel needs to find a tile's rows in token order
     std::vector<int32_t> tile_n0((size_t)toff);
     for (int h = 0; h < p->heads; ++h) {
         const HeadGeom& g = pl->heads[h];
         for (int32_t i = 0; i < g.n_tiles; ++i) {
-            const int o = g.grp == 2 ? i >> 1 : i, half = g.grp == 2 ? (i & 1) : 0;
-            const int tw = o % g.nw, th = (o / g.nw) % g.nh, tt = o / (g.nw * g.nh);
-            const int64_t t = (int64_t)tt * g.ot + half * g.ht, hh = (int64_t)th * g.oh + half * g.hh,
-                          w = (int64_t)tw * g.ow + half * g.hw;
-            tile_n0[(size_t)g.tile_off + i] = (int32_t)((t * p->H + hh) * p->W + w);
+            const int32_t n0 = veda::tile_anchor_token(g, i, p->T, p->H, p->W);
+            if (n0 < 0 || n0 >= (int64_t)p->T * p->H * p->W) {   // would send a kernel outside the tensor
+                delete pl;
+                veda::set_last_error("veda_plan_create: tile anchor outside the grid");
+                return VEDA_ERR_INVALID_ARG;
+            }
+            tile_n0[(size_t)g.tile_off + i] = n0;
         }
     }
 

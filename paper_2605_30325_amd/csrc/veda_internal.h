@@ -8,6 +8,7 @@
 #include <string>
 #include <vector>
 
+#include "geometry.h"
 #include "veda.h"
 
 namespace veda {
@@ -15,33 +16,6 @@ namespace veda {
 constexpr int kTile = 64;        // B: tokens per tile
 constexpr int kMaxHeads = 128;   // per-call tables passed by value are sized for this
 constexpr int kXcd = 8;          // accelerator dies (each with its own L2); workgroup i runs on die i % 8
-
-// Per-head geometry, one entry per head, in device memory (plan->d_heads).
-//
-// 128-token tiles are handled as two 64-slot halves: a tile of extents (ot,oh,ow) is cut across
-// its slowest axis of extent > 1, so that slots 0-63 are one half and slots 64-127 the other, and
-// the two halves are tiles 2o and 2o+1 of an "inner" geometry (grp = 2).  There pt,ph,pw are
-// the extents of a half, (ht,hh,hw) the token offset of the second half inside the whole tile,
-// and nt,nh,nw still count whole tiles.  For 64-token tiles grp = 1, (ot,oh,ow) = (pt,ph,pw)
-// and the offsets are zero.
-struct HeadGeom {
-    int32_t pt, ph, pw;      // extents of one 64-slot tile (or half tile)
-    int32_t nt, nh, nw;      // grid of whole tiles (ceil)
-    int32_t n_tiles;         // number of 64-slot tiles: grp*nt*nh*nw
-    int32_t tile_off;        // first global tile index of this head
-    int64_t score_off;       // first score element of this head (per batch)
-    int32_t score_blk_off;   // first 128x128 score block of this head
-    int32_t score_blk_dim;   // ceil(n_tiles / 128)
-    int32_t ot, oh, ow;      // extents of a whole tile
-    int32_t ht, hh, hw;      // token offset of the second half inside a whole tile
-    int32_t grp;             // 64-slot tiles per whole tile: 1 or 2
-    // Query tiles are processed two at a time by the bf16 attention and heat-map kernels.  Partners
-    // are neighbours along pair_ax (0 = t, 1 = h, 2 = w: the axis along which a tile is thinnest, so
-    // its neighbour is the closest one and keeps the most similar key tiles); a last layer without a
-    // partner is processed alone.  pair_ax = 3: the two halves of a 128-token tile.
-    int32_t pair_ax;
-    int32_t n_pairs;         // work items (pairs and partnerless tiles) of this head
-};
 
 #if defined(__HIPCC__)
 struct RecipTable { float v[2 * kTile + 1]; };  // v[c] = 1.0f / (float)c, computed on the host
@@ -92,7 +66,7 @@ struct veda_plan {
     veda_plan* inner = nullptr;
     veda::HeadGeom* d_heads = nullptr;  // device [heads]
     uint8_t* d_tile_head = nullptr;     // device [total_tiles]: head of each global tile
-    int32_t* d_tile_n0 = nullptr;       // device [total_tiles]: token index of slot 0 of each tile (always real)
+    int32_t* d_tile_n0 = nullptr;       // device [total_tiles]: anchor token of each tile (tile_anchor_token: always a real token)
     // Blocks of 64 consecutive tiles that never straddle two heads (the projection kernel's work
     // items): d_row_blk[x] = head << 24 | block index inside the head.
     int32_t* d_row_blk = nullptr;       // device [row_blocks]
