@@ -54,11 +54,14 @@ def score_scale_of(wl: wlm.Workload) -> float:
     return float(np.float32(1.0) / np.sqrt(np.float32(wl.latent_dim)))
 
 
-def run_gpu_path(wl: wlm.Workload, keep=None, k_per_head=None, want_lse=True) -> GpuRun:
+def run_gpu_path(wl: wlm.Workload, keep=None, k_per_head=None, want_lse=True, shapes=None,
+                 tile_tokens: int = 64) -> GpuRun:
+    """Stage by stage through the C ABI.  shapes / tile_tokens: other tile shapes than the workload's own
+    (128-token tiles: every stage works on whole tiles; the oracle takes the same shapes)."""
     dev = torch.device("cuda:0")
-    shapes = wlm.tile_shapes(wl)
+    shapes = wlm.tile_shapes(wl) if shapes is None else np.asarray(shapes, np.int32)
     q, k, v = wlm.make_qkv(wl, dev)
-    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=tile_tokens)
     kph = wlm.keep_budget(wl, keep, shapes) if k_per_head is None else np.asarray(k_per_head, np.int32)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
@@ -101,9 +104,12 @@ def check_head(run: GpuRun, head: int, batch: int = 0, attn_tiles: Optional[int]
     if check_layout:
         for name, x, order in (("q", qh, False), ("k", kh, False), ("v", vh, True)):
             ref, mask, cnt = vo.tile_layout(raw_numpy(x), grid, shape, channel_major=order)
-            got = raw_numpy(run.bufs[name + "t"][batch, toff:toff + nt]).reshape(ref.shape)
-            assert np.array_equal(got, ref), f"{tag}: tiled {name} differs"
-        gm = run.bufs["vm"][toff:toff + nt].cpu().numpy().view(np.uint64)
+            got = raw_numpy(run.bufs[name + "t"][batch, toff:toff + nt])
+            if order and plan.tile_tokens == 128:   # the library keeps [tile][half][channel][64]
+                ref = ref.reshape(nt, d, 2, 64).transpose(0, 2, 1, 3)
+            assert np.array_equal(got.reshape(ref.shape), ref), f"{tag}: tiled {name} differs"
+        words = plan.mask_words
+        gm = run.bufs["vm"][words * toff:words * (toff + nt)].cpu().numpy().view(np.uint64).reshape(mask.shape)
         assert np.array_equal(gm, mask), f"{tag}: valid_mask differs"
         assert np.array_equal(run.bufs["vc"][toff:toff + nt].cpu().numpy(), cnt), f"{tag}: valid_cnt differs"
 

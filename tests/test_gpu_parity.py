@@ -664,21 +664,94 @@ def test_wan1p3b_480p_sampled():
     _default_route_matches(run)
 
 
-@pytest.mark.parametrize("name", ["wan14b_480p", "wan14b_720p", "waver12b_720p_241f"])
-def test_large_configs_sampled(name):
+def _sampled_config(wl, keep=None, attn_tiles=6):
     """Full-size launch configuration; oracle on one head per tile shape and a seeded sample of
     query tiles (first and last tile always included)."""
-    wl = wlm.WORKLOADS[name]
-    _say(f"[parity] {wl.name}: generating inputs")
-    run = hz.run_gpu_path(wl, want_lse=False)
+    _say(f"[parity] {wl.name} keep {keep or wl.keep}: generating inputs")
+    run = hz.run_gpu_path(wl, keep=keep, want_lse=False)
     for h in hz.heads_by_shape(run):
-        _say(f"[parity] {wl.name} head {h} {tuple(run.shapes[h])}: checking")
-        _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=6)}")
+        _say(f"[parity] {wl.name} head {h} {tuple(run.shapes[h])} k {int(run.k_per_head[h])}: checking")
+        _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=attn_tiles)}")
     # every real token of every head was written (the output buffer starts as NaN)
     for h in range(wl.heads):
         assert torch.isfinite(run.out[0, h].float()).all(), h
     _say(f"[parity] {wl.name}: the default route of bench.py against this run")
     _default_route_matches(run)
+
+
+@pytest.mark.parametrize("name", ["wan14b_480p", "wan14b_720p", "waver12b_720p_241f"])
+def test_large_configs_sampled(name):
+    _sampled_config(wlm.WORKLOADS[name])
+
+
+@pytest.mark.parametrize("keep", [(20, 100), (10, 100)])
+def test_wan14b_720p_sparsity_sweep(keep):
+    """The 80 % and 90 % points of the 75,600-token configuration's sparsity sweep (its 95 % point is the
+    workload's default, above).  At these budgets stage 3 searches whole rows instead of sampling a pivot, and
+    the one-call route of stages 2+3 goes through its two-stage path: both must still give the oracle's lists."""
+    wl = wlm.WORKLOADS["wan14b_720p"]
+    assert keep in wl.keep_sweep and wl.keep in wl.keep_sweep
+    _sampled_config(wl, keep=keep, attn_tiles=4)
+
+
+def test_waver12b_dense_heads_equal_full_attention():
+    """0 % sparsity at 219,600 tokens: the full 24-head launch with k = N_T on the first head of every tile
+    shape (the other heads keep their 5 %), against plain softmax attention over all tokens (Eq. 1) on sampled
+    query tokens of the first and last tile and a seeded spread, and against the masked oracle on two tiles."""
+    wl = wlm.WORKLOADS["waver12b_720p_241f"]
+    shapes = wlm.tile_shapes(wl)
+    kph = wlm.keep_budget(wl, None, shapes)
+    nt = wlm.tiles_per_head(wl, shapes)
+    dense_heads = []
+    seen = set()
+    for h, sh in enumerate(map(tuple, shapes)):
+        if sh not in seen:
+            seen.add(sh)
+            dense_heads.append(h)
+            kph[h] = nt[h]
+    _say(f"[parity] {wl.name}: dense heads {dense_heads}, generating inputs")
+    run = hz.run_gpu_path(wl, k_per_head=kph, want_lse=False)
+    for h in range(wl.heads):
+        assert torch.isfinite(run.out[0, h].float()).all(), h
+    rng = np.random.default_rng(404)
+    for h in dense_heads:
+        shape = tuple(int(x) for x in shapes[h])
+        tile_of = vo.token_tile_map(wl.grid, shape)
+        first, last = np.flatnonzero(tile_of == 0), np.flatnonzero(tile_of == nt[h] - 1)
+        queries = np.unique(np.concatenate([first[:24], last[-24:], rng.choice(wl.tokens, 80, replace=False)]))
+        qf, kf, vf = (hz.to_f32_numpy(x[0, h]) for x in (run.q, run.k, run.v))
+        ref = vo.dense_attention(qf, kf, vf, run.softmax_scale, queries)
+        got = hz.to_f32_numpy(run.out[0, h])[queries].astype(np.float64)
+        err = np.abs(got - ref)
+        _say(f"[parity] {wl.name} dense head {h} {shape}: {len(queries)} tokens max_abs {err.max():.2e} "
+             f"mean_abs {err.mean():.2e}")
+        assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS
+        # the kept lists are 0..N_T-1 on every row of a dense head
+        r0 = run.plan.tile_offset[h]
+        rp = run.bufs["rp"][r0:r0 + nt[h] + 1].cpu().numpy().astype(np.int64)
+        assert np.all(np.diff(rp) == nt[h])
+        for row in (0, int(nt[h]) // 2, int(nt[h]) - 1):
+            lst = run.bufs["ci"][int(rp[row]):int(rp[row + 1])].cpu().numpy()
+            assert np.array_equal(lst, np.arange(nt[h]))
+    h = dense_heads[0]
+    _say(f"[parity] {wl.name} dense head {h}: stages against the oracle, two tiles of masked attention")
+    _say(f"[parity] {wl.name} dense head {h}: {hz.check_head(run, h, attn_tiles=2, check_layout=False)}")
+
+
+@pytest.mark.parametrize("name", ["wan14b_720p", "waver12b_720p_241f"])
+def test_128_token_tiles_at_full_size(name):
+    """The paper's tile size at a named configuration's full launch size: every 64-token shape doubled along t
+    (8x4x4, 2x8x8, 32x2x2), same kept fraction; one head per shape against the oracle on sampled tiles."""
+    wl = wlm.WORKLOADS[name]
+    shapes = wlm.tile_shapes(wl) * np.asarray([2, 1, 1], np.int32)
+    kph = wlm.keep_budget(wl, None, shapes)
+    _say(f"[parity] {wl.name} with 128-token tiles: generating inputs")
+    run = hz.run_gpu_path(wl, k_per_head=kph, want_lse=False, shapes=shapes, tile_tokens=128)
+    for h in hz.heads_by_shape(run):
+        _say(f"[parity] {wl.name} head {h} {tuple(run.shapes[h])} k {int(kph[h])}: checking")
+        _say(f"[parity] {wl.name} head {h}: {hz.check_head(run, h, attn_tiles=4)}")
+    for h in range(wl.heads):
+        assert torch.isfinite(run.out[0, h].float()).all(), h
 
 
 def test_rows_three_times_longer_than_any_named_workload():
