@@ -190,6 +190,23 @@ veda_status veda_tile_score_select_stats(const veda_plan*, const float* stats_q,
                                          const int32_t* k_per_head, int32_t* row_ptr, int32_t* col_idx,
                                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- stages 2 + 3 for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc ---------------------- */
+/* veda_tile_score_select_stats_noalloc = veda_tile_score_select_stats (same arguments, same row_ptr /
+ * col_idx bit for bit) with the workspace taken from a fixed array of VEDA_NOALLOC_SCRATCH_BYTES that
+ * the library holds in the memory of every GPU it is loaded on until the process ends.  The call
+ * makes no hipMalloc / hipFree and calls no allocating routine; it only enqueues kernels on `stream`.
+ * A plan with veda_plan_fused_workspace_bytes() above VEDA_NOALLOC_SCRATCH_BYTES is refused with
+ * VEDA_ERR_WORKSPACE (veda_last_error() names both sizes) and nothing is launched; the plan's device
+ * must be the current device.  Every call on a GPU uses that GPU's one array: calls that may overlap
+ * on one GPU (different streams, different threads) race on it and must be serialised by the
+ * caller.  The array keeps the last call's contents; nothing in it has to start at zero. */
+#define VEDA_NOALLOC_SCRATCH_BYTES ((size_t)128 << 20)
+veda_status veda_tile_score_select_stats_noalloc(const veda_plan*, const float* stats_q, const float* stats_k,
+                                                 const veda_mlp* phi_q, const veda_mlp* phi_k, float scale,
+                                                 const int32_t* k_per_head, int32_t* row_ptr, int32_t* col_idx,
+                                                 void* stream);
+
 /* ---- stage 4: block-sparse flash attention + un-tiling (Eq. 2; Sec. 4.3; Alg. 1 "UnTile") -- */
 /* q_tiled,k_tiled  VEDA_TOKEN_MAJOR; v_tiled VEDA_CHANNEL_MAJOR; valid_mask from stage 1.
  * row_ptr/col_idx  CSR lists as written by stage 3 (any order within a row is accepted, no

@@ -19,6 +19,7 @@
 //      and searched in full by the stage-3 search.  The result is the exact top-k either way.
 // Heads with short rows or large keep budgets (where stage 3 would not sample either) and
 // latents longer than 64 coordinates take the two-stage route through the scratch matrix.
+#include <atomic>
 #include <type_traits>
 
 #include "score_common.h"
@@ -374,6 +375,43 @@ static veda_status score_select(const veda_plan* pl, const veda_mlp* phi_q, cons
     return launch_status("fused_fallback_kernel");
 }
 
+// Scratch of the entry point that allocates nothing: a fixed array in every GPU's memory, held
+// from the moment the library is loaded on that GPU until the process ends.  In host code the
+// array's name is only a handle; its address on the current device comes from
+// hipGetSymbolAddress, once per device (noalloc_scratch below), and only that pointer is ever
+// handed to a kernel.
+constexpr size_t kNoAllocBytes = VEDA_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on GPU `device`, which must be the current device.  Resolved on
+// the first call per device (veda_plan_create makes that call), cached afterwards; two threads
+// racing on the first call store the same value.
+veda_status noalloc_scratch(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) {
+        set_last_error("no-allocation scratch: device index out of range");
+        return VEDA_ERR_UNSUPPORTED;
+    }
+    void* p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        int cur = -1;
+        VEDA_HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) {
+            set_last_error("no-allocation scratch: the plan's device is not the current device");
+            return VEDA_ERR_INVALID_ARG;
+        }
+        VEDA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) {
+            set_last_error("no-allocation scratch: hipGetSymbolAddress gave no address");
+            return VEDA_ERR_HIP;
+        }
+        g_scratch_ptr[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return VEDA_OK;
+}
+
 static veda_status check_pair(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k) {
     veda_status st = check_mlp(pl, phi_q);
     if (st == VEDA_OK) st = check_mlp(pl, phi_k);
@@ -418,5 +456,37 @@ extern "C" veda_status veda_tile_score_select_stats(const veda_plan* pl, const f
     if (!aligned16(stats_q) || !aligned16(stats_k) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
     const FusedSpace f = carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, workspace);
     if (!workspace || workspace_bytes < f.bytes) return VEDA_ERR_WORKSPACE;
+    return score_select(pl, phi_q, phi_k, scale, stats_q, stats_k, k_per_head, row_ptr, col_idx, f, (hipStream_t)stream);
+}
+
+extern "C" veda_status veda_tile_score_select_stats_noalloc(const veda_plan* pl, const float* stats_q,
+                                                            const float* stats_k, const veda_mlp* phi_q,
+                                                            const veda_mlp* phi_k, float scale,
+                                                            const int32_t* k_per_head, int32_t* row_ptr,
+                                                            int32_t* col_idx, void* stream) {
+    using namespace veda;
+    if (!pl || !stats_q || !stats_k || !k_per_head || !row_ptr || !col_idx) return VEDA_ERR_INVALID_ARG;
+    const veda_status st = check_pair(pl, phi_q, phi_k);
+    if (st != VEDA_OK) return st;
+    if (!aligned16(stats_q) || !aligned16(stats_k)) return VEDA_ERR_UNSUPPORTED;
+    const size_t need = carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, nullptr).bytes;
+    if (need > kNoAllocBytes) {
+        set_last_error("veda_tile_score_select_stats_noalloc: this plan needs " + std::to_string(need) +
+                       " bytes of scratch, the fixed array holds " + std::to_string(kNoAllocBytes) +
+                       "; use veda_tile_score_select_stats with a workspace of the caller's");
+        return VEDA_ERR_WORKSPACE;
+    }
+    int cur = -1;
+    VEDA_HIP_TRY(hipGetDevice(&cur));
+    if (cur != pl->device) {
+        set_last_error("veda_tile_score_select_stats_noalloc: the plan's device is not the current device");
+        return VEDA_ERR_INVALID_ARG;
+    }
+    void* ptr = nullptr;
+    const veda_status ss = noalloc_scratch(pl->device, &ptr);
+    if (ss != VEDA_OK) return ss;
+    // Nothing in the scratch has to start at zero: the marks of redone row groups are cleared by the
+    // first kernel of the call, every counter and flag of a real row is written before it is read.
+    const FusedSpace f = carve(pl, phi_q->out_dim, phi_q->hidden, phi_k->hidden, true, ptr);
     return score_select(pl, phi_q, phi_k, scale, stats_q, stats_k, k_per_head, row_ptr, col_idx, f, (hipStream_t)stream);
 }

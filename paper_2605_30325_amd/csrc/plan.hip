@@ -132,6 +132,15 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     const std::vector<int32_t> xcd_cum_pair = die_split(2, pl->xcd_max_pairs);
 
     hipError_t e = hipGetDevice(&pl->device);
+    if (e == hipSuccess) {
+        // set-up call of this device: the no-allocation entry point finds its scratch array resolved
+        void* unused = nullptr;
+        const veda_status ns = veda::noalloc_scratch(pl->device, &unused);
+        if (ns != VEDA_OK) {
+            delete pl;
+            return ns;
+        }
+    }
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_heads, sizeof(HeadGeom) * p->heads);
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_head, tile_head.size());
     if (e == hipSuccess) e = hipMalloc((void**)&pl->d_tile_n0, tile_n0.size() * sizeof(int32_t));

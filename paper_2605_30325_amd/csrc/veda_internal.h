@@ -100,6 +100,10 @@ inline veda_status launch_status(const char* what) {
     return e == hipSuccess ? VEDA_OK : hip_fail(e, what);
 }
 
+// Device address of the fixed scratch array of the no-allocation entry point (fused.hip) on GPU
+// `device`, which must be current; resolved once per device.
+veda_status noalloc_scratch(int device, void** out);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace veda

@@ -27,7 +27,8 @@ EXPORTS = (
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
-    "veda_tile_score_select", "veda_tile_score_select_stats", "veda_sparse_attn_fwd", "veda_sparse_attn_fwd_q_tokens",
+    "veda_tile_score_select", "veda_tile_score_select_stats", "veda_tile_score_select_stats_noalloc",
+    "veda_sparse_attn_fwd", "veda_sparse_attn_fwd_q_tokens",
     "veda_sparse_attn_fwd_qk_tokens", "veda_tile_heatmap",
     "veda_tile_recall", "veda_output_sqerr", "veda_status_string", "veda_last_error",
 )
@@ -102,6 +103,9 @@ def load():
     L.veda_tile_score_select_stats.argtypes = [vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
                                                C.POINTER(i32), vp, vp, vp, C.c_size_t, vp]
     L.veda_tile_score_select_stats.restype = C.c_int
+    L.veda_tile_score_select_stats_noalloc.argtypes = [vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
+                                                       C.POINTER(i32), vp, vp, vp]
+    L.veda_tile_score_select_stats_noalloc.restype = C.c_int
     L.veda_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides, vp, vp]
     L.veda_sparse_attn_fwd.restype = C.c_int
     L.veda_sparse_attn_fwd_q_tokens.argtypes = [vp, vp, veda_strides, vp, vp, vp, vp, vp, C.c_float, vp, veda_strides,
@@ -345,6 +349,28 @@ def veda_tile_score_select(plan: Plan, phi_q: Mlp, phi_k: Mlp, scale: float, k_p
                                              C.byref(sk), C.c_float(scale), kp, _ptr(row_ptr), _ptr(col_idx),
                                              _ptr(workspace), nbytes, _stream()), "veda_tile_score_select")
     return row_ptr, col_idx, workspace
+
+
+NOALLOC_SCRATCH_BYTES = 128 << 20
+
+
+def veda_tile_score_select_stats_noalloc(plan: Plan, phi_q: Mlp, phi_k: Mlp, scale: float, k_per_head: Sequence[int],
+                                         stats_q: torch.Tensor, stats_k: torch.Tensor, row_ptr: torch.Tensor,
+                                         col_idx: torch.Tensor):
+    """Stages 2 + 3 from descriptors with the library's fixed scratch array: the caller passes every
+    input and output, nothing is allocated here or in the library."""
+    k = np.ascontiguousarray(k_per_head, np.int32)
+    if k.size != plan.heads:
+        raise VedaError(VEDA_ERR_INVALID_ARG, "veda_tile_score_select_stats_noalloc",
+                        "k_per_head must have one entry per head")
+    sq, sk = phi_q.struct(), phi_k.struct()
+    status = load().veda_tile_score_select_stats_noalloc(
+        plan.handle, _ptr(stats_q), _ptr(stats_k), C.byref(sq), C.byref(sk), C.c_float(scale),
+        k.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(row_ptr), _ptr(col_idx), _stream())
+    if status == VEDA_ERR_WORKSPACE:
+        raise VedaError(status, "veda_tile_score_select_stats_noalloc", load().veda_last_error().decode())
+    _check(status, "veda_tile_score_select_stats_noalloc")
+    return row_ptr, col_idx
 
 
 def veda_sparse_attn_fwd(plan: Plan, q_tiled, k_tiled, v_tiled, valid_mask, row_ptr, col_idx,
