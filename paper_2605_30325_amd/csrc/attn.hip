@@ -127,9 +127,9 @@ static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const v
     if (q_tok && (!aligned16(q_tok) || (sq.b * es) % 16 || (sq.h * es) % 16 || (sq.n * es) % 16 ||
                   pl->prob.dtype != VEDA_BF16))
         return VEDA_ERR_UNSUPPORTED;
-    // a key row's byte offset from its tile's first token is kept in 32 bits
+    // a key row's byte offset from its tile's anchor token (plus a bias below 4 KiB) is kept in 32 bits
     if (k_tok && (!aligned16(k_tok) || (sk.b * es) % 16 || (sk.h * es) % 16 || (sk.n * es) % 16 ||
-                  pl->prob.dtype != VEDA_BF16 || pl->tokens() * sk.n * es >= ((int64_t)1 << 32)))
+                  pl->prob.dtype != VEDA_BF16 || pl->tokens() * sk.n * es >= ((int64_t)1 << 32) - 4096))
         return VEDA_ERR_UNSUPPORTED;
     // 128-token tiles: the kernel works on the 64-slot halves (inner plan), the CSR on whole tiles
     const veda_plan* ip = pl->inner ? pl->inner : pl;

@@ -94,6 +94,33 @@ __device__ __forceinline__ void dma16_to_lds(uint32_t lds_base, const void* base
                  : "memory", "m0");
 }
 
+// N (1, 2 or 4) such loads with one M0 set-up: load j lands at lds_base + 1024*j + 16*lane and
+// reads base + voff[j] + 1024*j -- the instruction's immediate offset moves the LDS address and
+// the global address alike (measured on gfx950), so voff[j] is passed with 1024*j already taken off.
+template <int N>
+__device__ __forceinline__ void dma16_group_to_lds(uint32_t lds_base, const void* base, const uint32_t (&voff)[N]) {
+    static_assert(N == 1 || N == 2 || N == 4, "1024*j must fit the 13-bit immediate offset");
+    if constexpr (N == 4) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %1, %5\n\t"
+                     "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+                     "global_load_lds_dwordx4 %4, %5 offset:3072"
+                     :
+                     : "s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(base)
+                     : "memory", "m0");
+    } else if constexpr (N == 2) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %1, %3\n\t"
+                     "global_load_lds_dwordx4 %2, %3 offset:1024"
+                     :
+                     : "s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(base)
+                     : "memory", "m0");
+    } else {
+        dma16_to_lds(lds_base, base, voff[0]);
+    }
+}
+
 // x of this lane and x of lane ^ 32, without a trip through LDS: the swap exchanges lanes 32-63
 // of its first operand with lanes 0-31 of its second, leaving (low half, low half) in one
 // register and (high half, high half) in the other.

@@ -17,8 +17,11 @@
 // accumulator registers run over keys, P^T in registers already is the B operand of the second
 // product.  K rows are loaded permuted by rho (bits 2,3 swapped) so that the eight keys a
 // lane-half owns are contiguous in the channel-major V tile.  One step of one wave:
-//     S^T block 0 (8 MFMA) | S^T block 1 (8 MFMA; the row maximum of block 0 in its shadow)
-//     row maximum, reference check, first 8 exponentials          (matrix pipe idle: other wave)
+//     S^T block 0 (8 MFMA; in their shadow the wave's share of the NEXT tiles' global->LDS loads
+//                  and the next step of the list walk)
+//     S^T block 1 (8 MFMA; in their shadow the row maximum of block 0 and, speculatively, the
+//                  first 8 exponentials)
+//     one comparison: need the reference move, has the tile padded slots?   (rarely: the slow path)
 //     4 x [ 4 MFMA of O^T += V^T P^T ; the next 8 exponentials in their shadow ]   (at raised wave priority)
 // K/V tiles are double buffered (2 x 32 KB at d = 128) and filled by direct global->LDS loads
 // issued one step ahead.
@@ -65,91 +68,63 @@ struct PairAddr {
 // MFMA holds the matrix pipe for 32 cycles, a plain VALU op issues in 4 and exp2 in 8, so the
 // vector work placed in a segment runs in the MFMA's shadow.  LDS operand reads are issued
 // kAhead MFMAs before their consumer.
-template <int D>
-__device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, uint64_t vm, uint32_t slot) {
-    constexpr int G = D / 16, NB = D / 32, kAhead = 6;
-    constexpr int kRowB = D * 2;
-    constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
-    const uint32_t ka = fa.k0 + slot, va = fa.v0 + slot;
+//
+// What a wave has to do besides its MFMAs is spread over their shadows, so that the stretches
+// in which it offers the matrix pipe nothing are short (the SIMD's other wave, from the second
+// resident workgroup, only fills them when it happens to be in a product of its own):
+//   - the step comes in pieces (begin, block0<0..kSideCalls-1>, finish) between which the caller
+//     places its per-step housekeeping (the next tiles' global->LDS loads, the next step of the
+//     list walk): common code of all waves, not a second copy for the waves that skip the step,
+//     which for the active ones runs in the shadow of block 0's MFMAs;
+//   - the row maximum of block 0 and the exponentials of its first 8 registers ride on block 1's
+//     MFMAs.  The exponentials are speculative: they assume that the reference need not move and
+//     that the tile has no padded slot.  After block 1 one comparison per lane (no exchange
+//     between the lane halves: the test is "any lane of the wave") decides; in the rare other
+//     case the step falls back to masking, the exact row maximum, moving the reference and
+//     forming those exponentials again.
+constexpr int kSideCalls = 4;
+
+template <int D> struct PairStep {
+    static constexpr int G = D / 16, NB = D / 32, kAhead = 6;
+    static constexpr int kRowB = D * 2;
+    static constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
+    static_assert(G % kSideCalls == 0, "block 0's MFMAs are dealt evenly to the side calls");
+    static constexpr int kSeg = G / kSideCalls;    // MFMAs of block 0 before each side call
+    bf16x8 fr[NF];
+    bf16x8 pf[4];     // P^T operand of key step kk = 2c + s2: registers 8*s2..8*s2+7 of block c
+    f32x16 s[2];
+    uint32_t ka, va;
     // Fragment f in issue order.  f < 2G: K fragment (c = f/G, t = f%G); then V^T fragments
     // (kk = (f-2G)/NB, nb = (f-2G)%NB).
 #define VEDA_KF(f) lds_read16((ka ^ (uint32_t)(((f) % G) << 5)) + (uint32_t)(((f) / G) * 32 * kRowB))
 #define VEDA_VF(f) lds_read16((va ^ (uint32_t)(((f) / NB) << 5)) + (uint32_t)(((f) % NB) * 4096))
 #define VEDA_FRAG(f) ((f) < 2 * G ? VEDA_KF((f) < 2 * G ? (f) : 0) : VEDA_VF((f) < 2 * G ? 0 : (f) - 2 * G))
-    bf16x8 fr[NF];
-    bf16x8 pf[4];     // P^T operand of key step kk = 2c + s2: registers 8*s2..8*s2+7 of block c
-    f32x16 s[2];
+
+    // The first operand reads of the step.
+    __device__ __forceinline__ void begin(const PairAddr& fa, uint32_t slot) {
+        ka = fa.k0 + slot;
+        va = fa.v0 + slot;
 #pragma unroll
-    for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f);
-    __builtin_amdgcn_sched_barrier(0);
-    // S^T block 0
-#pragma unroll
-    for (int f = 0; f < G; ++f) {
-        fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], f == 0 ? st.start : s[0], 0, 0, 0);
+        for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f);
         __builtin_amdgcn_sched_barrier(0);
     }
-    // S^T block 1; the row maximum of block 0 rides along from the third MFMA on (block 0's
-    // last MFMA needs that long to retire)
-    float mx = -INFINITY;
+
+    // MFMAs kSeg*H .. kSeg*H + kSeg - 1 of S^T block 0; side call H follows them in the caller.
+    template <int H> __device__ __forceinline__ void block0(const PairState<D>& st) {
 #pragma unroll
-    for (int f = G; f < 2 * G; ++f) {
-        fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], f == G ? st.start : s[1], 0, 0, 0);
-        if (f - G >= 2) {
-            constexpr int per = 16 / (G - 2) + (16 % (G - 2) ? 1 : 0);
-#pragma unroll
-            for (int e = 0; e < per; ++e) {
-                const int i = (f - G - 2) * per + e;
-                if (i < 16) mx = fmaxf(mx, s[0][i]);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-    if (vm != ~0ull) {
-        // Edge tile: padded key slots get -inf.  Register i of key block c is key slot
-        // 32c + 16*(i/8) + 8*hh + (i%8); the lane-dependent part is shifted out first so the
-        // per-register tests use constant bit positions.  The empty asm keeps this a real
-        // branch: if-converted into the main block it would cost ~90 vector ops on every step.
-        asm volatile("" ::: "memory");
-        mx = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * fa.hh);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (!((half >> (16 * (i >> 3) + (i & 7))) & 1u)) s[c][i] = -INFINITY;
-                mx = fmaxf(mx, s[c][i]);
-            }
+        for (int f = kSeg * H; f < kSeg * (H + 1); ++f) {
+            fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], f == 0 ? st.start : s[0], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    mx = max_with_other_half(mx);   // row maximum relative to the reference
-    if (!st.started || __any(mx > kPairSlack)) {
-        // Move the reference of every row whose maximum is above it (first step: to the
-        // maximum itself, up or down).
-        float delta = st.started ? fmaxf(mx, 0.0f) : mx;
-        delta = delta == -INFINITY ? 0.0f : delta;
-        const float alpha = st.started ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // O = l = 0 before
-        st.ref += delta;
-        st.l_run *= alpha;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st.start[i] = -st.ref;
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[c][i] -= delta;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) st.o[nb][i] *= alpha;
-        st.started = true;
-    }
-    float psum = 0.0f;
-    // P^T of key step kk: exponentials of registers 8*(kk%2)..+7 of block kk/2
-    // two scores at a time, so that the pair is rounded to bf16 by one packed conversion
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+    // S^T block 1, the softmax and O^T += V^T P^T.
+    __device__ __forceinline__ void finish(PairState<D>& st, const PairAddr& fa, uint64_t vm) {
+        float psum = 0.0f;
+        // P^T of key step kk: exponentials of registers 8*(kk%2)..+7 of block kk/2
+        // two scores at a time, so that the pair is rounded to bf16 by one packed conversion
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 #define VEDA_EXP(kk, e)                                                                         \
     do {                                                                                        \
         const float p0_ = __builtin_amdgcn_exp2f(s[(kk) >> 1][8 * ((kk) & 1) + (e)]);           \
@@ -160,34 +135,100 @@ __device__ __forceinline__ void pair_step(PairState<D>& st, const PairAddr& fa, 
         pf[kk][e] = pr_[0];                                                                     \
         pf[kk][(e) + 1] = pr_[1];                                                               \
     } while (0)
+        // S^T block 1.  Block 0's last MFMA needs two more to retire; then its row maximum (kMaxSeg
+        // MFMAs) and the speculative exponentials of its first 8 registers (the rest) ride along.
+        constexpr int kMaxSeg = G >= 8 ? 2 : 1, kExpSeg = G - 2 - kMaxSeg;
+        static_assert(kExpSeg >= 1 && 8 % kExpSeg == 0 && (8 / kExpSeg) % 2 == 0, "exponentials come in pairs");
+        float mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) VEDA_EXP(0, e);
-    // The wave that has reached its O^T products goes first at the issue port: the other wave
-    // of the SIMD (in its own softmax section, all vector ops) otherwise delays these MFMAs and
-    // the matrix pipe idles.  Measured: 6 % fewer cycles for the whole kernel.
-    __builtin_amdgcn_s_setprio(1);
-    __builtin_amdgcn_sched_barrier(0);
-    // O^T += V^T P^T; the 8 exponentials of the next key step are spread over this key step's
-    // NB MFMAs
+        for (int f = G; f < 2 * G; ++f) {
+            fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], f == G ? st.start : s[1], 0, 0, 0);
+            const int i = f - G - 2;
+            if (i >= 0 && i < kMaxSeg) {
 #pragma unroll
-    for (int g = 0; g < 4 * NB; ++g) {
-        const int f = 2 * G + g;
-        if (f + kAhead < NF) fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-        const int kk = g / NB, nb = g % NB;
-        st.o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], pf[kk], st.o[nb], 0, 0, 0);
-        if (kk < 3) {
+                for (int e = i * (16 / kMaxSeg); e < (i + 1) * (16 / kMaxSeg); ++e) mx = fmaxf(mx, s[0][e]);
+            }
+            if (i >= kMaxSeg) {
 #pragma unroll
-            for (int e = nb * (8 / NB); e < (nb + 1) * (8 / NB); e += 2) VEDA_EXP(kk + 1, e);
+                for (int e = (i - kMaxSeg) * (8 / kExpSeg); e < (i - kMaxSeg + 1) * (8 / kExpSeg); e += 2) VEDA_EXP(0, e);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
+        // this lane's half of the row maximum is enough to see whether ANY row of the wave outgrew its reference
+        if (__builtin_expect(vm != ~0ull || !st.started || __any(mx > kPairSlack), 0)) {
+            // The empty asm keeps this a real branch: if-converted into the main block its ~150 vector
+            // ops would run on every step.
+            asm volatile("" ::: "memory");
+            if (vm != ~0ull) {
+                // Edge tile: padded key slots get -inf.  Register i of key block c is key slot
+                // 32c + 16*(i/8) + 8*hh + (i%8); the lane-dependent part is shifted out first so the
+                // per-register tests use constant bit positions.
+                mx = -INFINITY;
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * fa.hh);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        if (!((half >> (16 * (i >> 3) + (i & 7))) & 1u)) s[c][i] = -INFINITY;
+                        mx = fmaxf(mx, s[c][i]);
+                    }
+                }
+            }
+            mx = max_with_other_half(mx);   // row maximum relative to the reference
+            if (!st.started || __any(mx > kPairSlack)) {
+                // Move the reference of every row whose maximum is above it (first step: to the
+                // maximum itself, up or down).
+                float delta = st.started ? fmaxf(mx, 0.0f) : mx;
+                delta = delta == -INFINITY ? 0.0f : delta;
+                const float alpha = st.started ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // O = l = 0 before
+                st.ref += delta;
+                st.l_run *= alpha;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) st.start[i] = -st.ref;
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s[c][i] -= delta;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) st.o[nb][i] *= alpha;
+                st.started = true;
+            }
+            psum = 0.0f;   // the speculative exponentials are void
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) VEDA_EXP(0, e);
+        }
+        // The wave that has reached its O^T products goes first at the issue port: the other wave
+        // of the SIMD (in its own softmax section, all vector ops) otherwise delays these MFMAs and
+        // the matrix pipe idles.  Measured: 6 % fewer cycles for the whole kernel.
+        __builtin_amdgcn_s_setprio(1);
         __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_s_setprio(0);
-    st.l_run += psum;
+        // O^T += V^T P^T; the 8 exponentials of the next key step are spread over this key step's
+        // NB MFMAs
+#pragma unroll
+        for (int g = 0; g < 4 * NB; ++g) {
+            const int f = 2 * G + g;
+            if (f + kAhead < NF) fr[f + kAhead] = VEDA_FRAG(f + kAhead);
+            const int kk = g / NB, nb = g % NB;
+            st.o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], pf[kk], st.o[nb], 0, 0, 0);
+            if (kk < 3) {
+#pragma unroll
+                for (int e = nb * (8 / NB); e < (nb + 1) * (8 / NB); e += 2) VEDA_EXP(kk + 1, e);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        st.l_run += psum;
 #undef VEDA_EXP
+    }
 #undef VEDA_FRAG
 #undef VEDA_KF
 #undef VEDA_VF
-}
+};
 
 // After the last step: normalise, transpose through LDS and scatter the real rows of the
 // workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, then lse_s and tok_s.
@@ -323,9 +364,13 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     // global -> LDS copy plan.  One wave instruction fills 1 KB of LDS, lane i at byte 16*i, so
     // the swizzle is applied on the global side: each lane fetches the chunk that belongs at
     // its fixed LDS position.  Wave w issues instructions w*kLoads .. w*kLoads+kLoads-1 of each
-    // tile.
+    // tile, all with one LDS base: instruction j carries the immediate offset 1024*j, which the
+    // hardware adds to the LDS address AND to the global address, so every per-lane global offset
+    // below is stored with 1024*j taken off again (plus kBias where it could go negative, the tile's
+    // base address being lowered by the same amount).
+    constexpr uint32_t kBias = kTokK ? 1024u * (kLoads - 1) : 0u;
     uint32_t k_src[kLoads], v_src[kLoads];
-    uint32_t k_src0[kLoads];   // kTokK: the same chunk of the tile's slot 0
+    uint32_t k_src0[kLoads];   // kTokK: the same chunk of the tile's anchor row
     int k_row[kLoads];
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
@@ -333,34 +378,35 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
         const int krow = inst * (1024 / kRowB) + lane / kKChunks, kpos = lane % kKChunks;
         const uint32_t chunk = (uint32_t)((kpos ^ (rho(krow & 31) & (kKChunks - 1))) << 4);
         k_row[j] = krow;
-        k_src0[j] = chunk;
-        if (kTokK) {   // byte offset of the row's token from the tile's first token (host checked: fits 32 bits)
+        k_src0[j] = chunk + kBias - 1024u * j;
+        if (kTokK) {   // byte offset of the row's token from the tile's anchor token (host checked: fits 32 bits)
             const int lw = krow % hg.pw, lh = (krow / hg.pw) % hg.ph, lt = krow / (hg.pw * hg.ph);
-            k_src[j] = (uint32_t)((((int64_t)lt * a.H + lh) * a.W + lw) * a.sk_n) + chunk;
+            k_src[j] = (uint32_t)((((int64_t)lt * a.H + lh) * a.W + lw) * a.sk_n) + chunk + kBias - 1024u * j;
         } else {
-            k_src[j] = krow * kRowB + chunk;
+            k_src[j] = krow * kRowB + chunk - 1024u * j;
         }
         const int vrow = inst * 8 + (lane >> 3), vpos = lane & 7;
-        v_src[j] = vrow * 128 + ((vpos ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4);
+        v_src[j] = vrow * 128 + ((vpos ^ (((vrow >> 1) & 7) ^ ((vrow & 1) << 2))) << 4) - 1024u * j;
     }
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t wave_lds = smem_base + (uint32_t)wave * (kLoads * 1024);
-#define VEDA_LOAD_KV(E, SLOT)                                                                              \
-    do {                                                                                                   \
-        const int j_tile = (E).j;                                                                          \
-        const char* ksrc_ = kTokK ? kt + (int64_t)(E).n0 * a.sk_n : kt + (int64_t)j_tile * kKBytes;        \
-        const char* vsrc_ = vt + (int64_t)j_tile * kVBytes;                                                \
-        if (kTokK && (E).vm != ~0ull) {   /* edge tile: padded rows have no token */                       \
-            _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                             \
-                dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_,                                  \
-                             ((E).vm >> k_row[j]) & 1ull ? k_src[j] : k_src0[j]);                          \
-        } else {                                                                                           \
-            _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                             \
-                dma16_to_lds(wave_lds + (SLOT) * kSlot + j * 1024, ksrc_, k_src[j]);                       \
-        }                                                                                                  \
-        _Pragma("unroll") for (int j = 0; j < kLoads; ++j)                                                 \
-            dma16_to_lds(wave_lds + (SLOT) * kSlot + kKBytes + j * 1024, vsrc_, v_src[j]);                 \
-    } while (0)
+    // The K tile (which = 0) or the V^T tile (which = 1) of step e into LDS slot `sl`.
+    auto load_tile = [&](const MergedStep& e, int sl, int what) __attribute__((always_inline)) {
+        if (what == 0) {
+            const char* src = (kTokK ? kt + (int64_t)e.n0 * a.sk_n : kt + (int64_t)e.j * kKBytes) - kBias;
+            const uint32_t dst = wave_lds + (uint32_t)sl * kSlot;
+            if (kTokK && e.vm != ~0ull) {   // edge tile: padded rows have no token
+                uint32_t off[kLoads];
+#pragma unroll
+                for (int j = 0; j < kLoads; ++j) off[j] = (e.vm >> k_row[j]) & 1ull ? k_src[j] : k_src0[j];
+                dma16_group_to_lds<kLoads>(dst, src, off);
+            } else {
+                dma16_group_to_lds<kLoads>(dst, src, k_src);
+            }
+        } else {
+            dma16_group_to_lds<kLoads>(wave_lds + (uint32_t)sl * kSlot + kKBytes, vt + (int64_t)e.j * kVBytes, v_src);
+        }
+    };
     // All of this wave's LDS-bound loads have landed (vmcnt 0), then meet the other waves.
 #define VEDA_LOADS_DONE_BARRIER()   \
     do {                            \
@@ -378,55 +424,93 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     // lists, as stage 3 writes them, share the most; any order stays correct.)
     // The list heads are kept as (raw loaded value, in-range flag) and only combined when the
     // next step is formed, one step later: the scalar loads get a whole step to return.
+    // A step is formed in two halves (next_head: which tile and who keeps it; next_advance: move
+    // the list positions and fetch the new heads) so that each fits the shadow of one MFMA.
+    // Everything of the walk is kept in 32-bit integers (flags as 0/1, never as booleans) and the
+    // step's flags pass through readfirstlane: the walk then stays on the scalar unit and the
+    // branches on it are scalar branches.
     constexpr int kEnd = 0x7fffffff;
     int ia = 0, ib = 0;
     int rawA = colsA[0], rawB = colsB[0];
-    bool okA = nA > 0, okB = nB > 0;
-    int gh = 0;   // grouped walk: which half of the current entry comes next
-#define VEDA_NEXT_STEP(e)                                                            \
-    do {                                                                             \
-        if (kGrouped) {                                                              \
-            (e).j = okA ? 2 * rawA + gh : 0;                                         \
-            (e).fl = okA ? 3 : 0;                                                    \
-            (e).vm = vmask[(e).j];                                                   \
-            (e).n0 = kTokK ? n0s[(e).j] : 0;                                         \
-            ia += gh;                                                                \
-            gh ^= 1;                                                                 \
-            okA = ia < nA;                                                           \
-            rawA = colsA[okA ? ia : 0];                                              \
-        } else {                                                                     \
-            const int headA_ = okA ? rawA : kEnd, headB_ = okB ? rawB : kEnd;        \
-            const int j_ = headA_ < headB_ ? headA_ : headB_;                        \
-            const bool live_ = j_ != kEnd;                                           \
-            const int ta_ = (live_ && headA_ == j_) ? 1 : 0;                         \
-            const int tb_ = (live_ && headB_ == j_) ? 1 : 0;                         \
-            (e).j = live_ ? j_ : 0;                                                  \
-            (e).fl = ta_ | (tb_ << 1);                                               \
-            (e).vm = vmask[(e).j];                                                   \
-            (e).n0 = kTokK ? n0s[(e).j] : 0;                                         \
-            ia += ta_;                                                               \
-            ib += tb_;                                                               \
-            okA = ia < nA;                                                           \
-            okB = ib < nB;                                                           \
-            rawA = colsA[okA ? ia : 0];                                              \
-            rawB = colsB[okB ? ib : 0];                                              \
-        }                                                                            \
-    } while (0)
+    int okA = nA > 0 ? 1 : 0, okB = nB > 0 ? 1 : 0;
+    int gh = 0;         // grouped walk: which half of the current entry comes next
+    int ta = 0, tb = 0; // this step consumes the head of list A / B
+    auto next_head = [&](MergedStep& e) __attribute__((always_inline)) {
+        int j, fl;
+        if (kGrouped) {
+            j = okA ? 2 * rawA + gh : 0;
+            fl = okA ? 3 : 0;
+            ta = gh;
+        } else {
+            const int headA = okA ? rawA : kEnd, headB = okB ? rawB : kEnd;
+            const int jm = headA < headB ? headA : headB;
+            const int live = jm != kEnd ? 1 : 0;
+            ta = headA == jm ? live : 0;
+            tb = headB == jm ? live : 0;
+            j = live ? jm : 0;
+            fl = ta | (tb << 1);
+        }
+        e.j = __builtin_amdgcn_readfirstlane(j);
+        e.fl = __builtin_amdgcn_readfirstlane(fl);
+        e.vm = vmask[e.j];
+        e.n0 = kTokK ? n0s[e.j] : 0;
+    };
+    auto next_advance = [&]() __attribute__((always_inline)) {
+        ia += ta;
+        okA = ia < nA ? 1 : 0;
+        rawA = colsA[okA ? ia : 0];
+        if (kGrouped) {
+            gh ^= 1;
+        } else {
+            ib += tb;
+            okB = ib < nB ? 1 : 0;
+            rawB = colsB[okB ? ib : 0];
+        }
+    };
 
     // Step s (P = s & 1) computes on slot P while the tiles of step s+1 land in slot P^1.
     const int my_bit = 1 << which;
-    MergedStep e0, e1;
-    VEDA_NEXT_STEP(e0);
-    VEDA_NEXT_STEP(e1);
-    if (e0.fl) VEDA_LOAD_KV(e0, 0);
+    MergedStep e0, e1, e2;
+    next_head(e0);
+    next_advance();
+    next_head(e1);
+    next_advance();
+    if (e0.fl) {
+        load_tile(e0, 0, 0);
+        load_tile(e0, 0, 1);
+    }
     VEDA_LOADS_DONE_BARRIER();   // also the Q loads: nothing vector-memory is pending below
 
+    // One step.  A wave whose query tile keeps the current key tile does its housekeeping (loads of
+    // the next tiles, next step of the walk) between the pieces of its step; a wave that skips the
+    // step does it on its own.  (Two separate conditionals with an opaque flag rather than
+    // if/else: with an else branch the register allocator keeps a second copy of the accumulators.)
 #define VEDA_STEP(P)                                                                                     \
     do {                                                                                                 \
-        if (e1.fl) VEDA_LOAD_KV(e1, (P) ^ 1);                                                            \
-        MergedStep e2;                                                                                   \
-        VEDA_NEXT_STEP(e2);                                                                              \
-        if (e0.fl & my_bit) pair_step<D>(st, fa, e0.vm, (uint32_t)((P) * kSlot));                        \
+        int todo = 1;                                                                                    \
+        if (__builtin_expect((e0.fl & my_bit) != 0, 1)) {                                                \
+            PairStep<D> w;                                                                               \
+            w.begin(fa, (uint32_t)((P) * kSlot));                                                        \
+            w.template block0<0>(st);                                                                    \
+            if (e1.fl) load_tile(e1, (P) ^ 1, 0);                                                        \
+            w.template block0<1>(st);                                                                    \
+            if (e1.fl) load_tile(e1, (P) ^ 1, 1);                                                        \
+            w.template block0<2>(st);                                                                    \
+            next_head(e2);                                                                               \
+            w.template block0<3>(st);                                                                    \
+            next_advance();                                                                              \
+            w.finish(st, fa, e0.vm);                                                                     \
+            todo = 0;                                                                                    \
+        }                                                                                                \
+        asm volatile("" : "+s"(todo));                                                                   \
+        if (todo) {                                                                                      \
+            if (e1.fl) {                                                                                 \
+                load_tile(e1, (P) ^ 1, 0);                                                               \
+                load_tile(e1, (P) ^ 1, 1);                                                               \
+            }                                                                                            \
+            next_head(e2);                                                                               \
+            next_advance();                                                                              \
+        }                                                                                                \
         e0 = e1; e1 = e2;                                                                                \
         VEDA_LOADS_DONE_BARRIER();                                                                       \
     } while (0)
@@ -436,8 +520,6 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
         VEDA_STEP(1);
     }
 #undef VEDA_STEP
-#undef VEDA_NEXT_STEP
-#undef VEDA_LOAD_KV
 #undef VEDA_LOADS_DONE_BARRIER
 
     finish_pair<D>(st, a, hg, smem, head, qiA, qiB, hasB, b, tid, which, r, lq, hh);
