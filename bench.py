@@ -167,7 +167,6 @@ def main():
     B = args.tile_tokens
     if B == 128:
         shapes = shapes * np.asarray([2, 1, 1], np.int32)
-        args.unfused = True          # the descriptor-during-gather route is for 64-token tiles
     q, k, v = wlm.make_qkv(wl, dev)
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=B)
     kph = wlm.keep_budget(wl, keep, shapes)

@@ -66,8 +66,7 @@ typedef struct {
  *   a token-major tiled tensor is [tile][128][channel] as for any B;
  *   a channel-major tiled tensor is [tile][half][channel][64];
  *   valid_mask holds two u64 words per tile (word w covers slots 64w..64w+63);
- *   veda_tile_layout needs valid_mask whenever valid_cnt is asked for;
- *   veda_tile_layout_stats is for 64-token tiles only. */
+ *   veda_tile_layout needs valid_mask whenever valid_cnt is asked for. */
 
 /* Element strides of a token-order tensor x[b][h][n][c]; the channel stride is 1.
  * Each stride must be a multiple of 16 bytes and the base 16-byte aligned. */

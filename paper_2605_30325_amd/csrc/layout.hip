@@ -104,8 +104,12 @@ __global__ void valid_cnt_pairs_kernel(const uint64_t* __restrict__ mask, int32_
 // bit-identical to the ones it derives from the tiled tensor.  A workgroup holds 256 / (D / kN)
 // consecutive global tiles (they may belong to different heads).
 // kWrite = false: descriptors (and masks) only, the tiled tensor is not written.
+// GRP = 2: 128-token tiles.  `heads`, `tile_head` and total_tiles are then those of the 64-slot
+// halves (halves 2g, 2g+1 of whole tile g); a thread walks the 128 slots of a whole tile in order
+// (first half, then second half: the oracle's raster slot order), the mask has two words per tile,
+// and the tiled output [tile][128][channel] is the two halves back to back.
 #pragma clang fp contract(off)
-template <typename E, int D, bool kWrite>
+template <typename E, int D, bool kWrite, int GRP>
 __global__ __launch_bounds__(256) void layout_stats_kernel(
     const HeadGeom* __restrict__ heads, const uint8_t* __restrict__ tile_head,
     const char* __restrict__ x, int64_t sb, int64_t sh, int64_t sn, char* __restrict__ out,
@@ -115,50 +119,58 @@ __global__ __launch_bounds__(256) void layout_stats_kernel(
     constexpr int kTpt = D / kN;            // threads per tile
     constexpr int kTiles = 256 / kTpt;      // tiles per workgroup
     constexpr int kRowBytes = D * (int)sizeof(E);
-    __shared__ int tok[kTiles][kTile];
+    constexpr int kSlots = kTile * GRP;     // slots of a whole tile
+    __shared__ int tok[kTiles][kSlots];
+    const int64_t whole_tiles = total_tiles / GRP;
     const int64_t g0 = (int64_t)blockIdx.x * kTiles;
     const int b = blockIdx.y;
-    for (int e = threadIdx.x; e < kTiles * kTile; e += 256) {
-        const int tl = e / kTile, l = e % kTile;
-        const int64_t g = g0 + tl;
+    for (int e = threadIdx.x; e < kTiles * kSlots; e += 256) {
+        const int tl = e / kSlots, l = e % kSlots;
+        const int64_t gi = (g0 + tl) * GRP + l / kTile;   // the 64-slot tile this slot belongs to
         int n = -1;
-        if (g < total_tiles) {
-            const HeadGeom hg = heads[tile_head[g]];
-            n = slot_token(hg, (int)(g - hg.tile_off), l, T, H, W);
+        if (g0 + tl < whole_tiles) {
+            const HeadGeom hg = heads[tile_head[gi]];
+            n = slot_token(hg, (int)(gi - hg.tile_off), l % kTile, T, H, W);
         }
         tok[tl][l] = n;
     }
     __syncthreads();
     const int tl = threadIdx.x / kTpt, chunk = threadIdx.x % kTpt;
     const int64_t g = g0 + tl;
-    if (g >= total_tiles) return;
-    const int head = tile_head[g];
+    if (g >= whole_tiles) return;
+    const int head = tile_head[g * GRP];
     const char* xb = x + b * sb + head * sh + chunk * 16;
-    const int64_t row = (int64_t)b * total_tiles + g;
-    char* ob = out + row * (int64_t)kTile * kRowBytes + chunk * 16;
+    const int64_t row = (int64_t)b * whole_tiles + g;
+    char* ob = out + row * (int64_t)kSlots * kRowBytes + chunk * 16;
     float sum[kN], mx[kN], mn[kN];
 #pragma unroll
     for (int j = 0; j < kN; ++j) { sum[j] = 0.0f; mx[j] = -INFINITY; mn[j] = INFINITY; }
-    uint64_t mask = 0ull;
-#pragma unroll 8
-    for (int l = 0; l < kTile; ++l) {
-        const int n = tok[tl][l];
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (n >= 0) {
-            v = *reinterpret_cast<const uint4*>(xb + (int64_t)n * sn);
-            mask |= 1ull << l;
-            float f[kN];
-            Chunk<E>::unpack(v, f);
+    uint64_t mask[GRP];
 #pragma unroll
-            for (int j = 0; j < kN; ++j) {
-                sum[j] = sum[j] + f[j];
-                mx[j] = f[j] > mx[j] ? f[j] : mx[j];
-                mn[j] = f[j] < mn[j] ? f[j] : mn[j];
+    for (int w = 0; w < GRP; ++w) {
+        mask[w] = 0ull;
+#pragma unroll 8
+        for (int l = 0; l < kTile; ++l) {
+            const int n = tok[tl][w * kTile + l];
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (n >= 0) {
+                v = *reinterpret_cast<const uint4*>(xb + (int64_t)n * sn);
+                mask[w] |= 1ull << l;
+                float f[kN];
+                Chunk<E>::unpack(v, f);
+#pragma unroll
+                for (int j = 0; j < kN; ++j) {
+                    sum[j] = sum[j] + f[j];
+                    mx[j] = f[j] > mx[j] ? f[j] : mx[j];
+                    mn[j] = f[j] < mn[j] ? f[j] : mn[j];
+                }
             }
+            if (kWrite) *reinterpret_cast<uint4*>(ob + (w * kTile + l) * kRowBytes) = v;
         }
-        if (kWrite) *reinterpret_cast<uint4*>(ob + l * kRowBytes) = v;
     }
-    const int cnt = __popcll(mask);
+    int cnt = 0;
+#pragma unroll
+    for (int w = 0; w < GRP; ++w) cnt += __popcll(mask[w]);
     const float inv = recip.v[cnt];
     float* z = stats + row * (3 * D) + chunk * kN;
 #pragma unroll
@@ -168,7 +180,10 @@ __global__ __launch_bounds__(256) void layout_stats_kernel(
         z[2 * D + j] = mn[j];
     }
     if (chunk == 0 && b == 0) {
-        if (valid_mask) valid_mask[g] = mask;
+        if (valid_mask) {
+#pragma unroll
+            for (int w = 0; w < GRP; ++w) valid_mask[g * GRP + w] = mask[w];
+        }
         if (valid_cnt) valid_cnt[g] = cnt;
     }
 }
@@ -220,7 +235,6 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
                                               void* stream) {
     using namespace veda;
     if (!pl || !x || !stats) return VEDA_ERR_INVALID_ARG;   // x_tiled may be null: descriptors only
-    if (pl->inner) return VEDA_ERR_UNSUPPORTED;   // 64-token tiles only
     const int es = pl->elem_size();
     const int d = pl->prob.head_dim;
     if (sx.n < d || sx.b < 0 || sx.h < 0) return VEDA_ERR_INVALID_ARG;
@@ -233,23 +247,29 @@ extern "C" veda_status veda_tile_layout_stats(const veda_plan* pl, const void* x
     RecipTable recip;
     recip.v[0] = 0.0f;
     for (int c = 1; c <= 2 * kTile; ++c) recip.v[c] = 1.0f / (float)c;
+    // 128-token tiles (bf16 plans only): the kernel walks the two 64-slot halves of every whole tile
+    const veda_plan* ip = pl->inner ? pl->inner : pl;
+#define VEDA_LAUNCH_LS2(E, D, WR, GRP)                                                                    \
+    hipLaunchKernelGGL((layout_stats_kernel<E, D, WR, GRP>), grid, dim3(256), 0, st, ip->d_heads,         \
+                       ip->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, stats, ip->total_tiles, T, H, W, \
+                       valid_mask, valid_cnt, recip)
 #define VEDA_LAUNCH_LS(E, D)                                                                              \
     do {                                                                                                  \
         constexpr int tiles = 256 / (D / Chunk<E>::kN);                                                   \
         dim3 grid((unsigned)((pl->total_tiles + tiles - 1) / tiles), (unsigned)pl->prob.batch);           \
-        if (x_tiled)                                                                                      \
-            hipLaunchKernelGGL((layout_stats_kernel<E, D, true>), grid, dim3(256), 0, st, pl->d_heads,    \
-                               pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)x_tiled, stats,        \
-                               pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                   \
-        else                                                                                              \
-            hipLaunchKernelGGL((layout_stats_kernel<E, D, false>), grid, dim3(256), 0, st, pl->d_heads,   \
-                               pl->d_tile_head, (const char*)x, sb, sh, sn, (char*)nullptr, stats,        \
-                               pl->total_tiles, T, H, W, valid_mask, valid_cnt, recip);                   \
+        if (pl->inner) {                                                                                  \
+            if (x_tiled) VEDA_LAUNCH_LS2(E, D, true, 2);                                                  \
+            else VEDA_LAUNCH_LS2(E, D, false, 2);                                                         \
+        } else {                                                                                          \
+            if (x_tiled) VEDA_LAUNCH_LS2(E, D, true, 1);                                                  \
+            else VEDA_LAUNCH_LS2(E, D, false, 1);                                                         \
+        }                                                                                                 \
     } while (0)
     if (es == 2 && d == 128) VEDA_LAUNCH_LS(uint16_t, 128);
     else if (es == 2 && d == 64) VEDA_LAUNCH_LS(uint16_t, 64);
     else if (es == 4 && d == 128) VEDA_LAUNCH_LS(uint32_t, 128);
     else VEDA_LAUNCH_LS(uint32_t, 64);
 #undef VEDA_LAUNCH_LS
+#undef VEDA_LAUNCH_LS2
     return launch_status("veda_tile_layout_stats");
 }

@@ -257,9 +257,10 @@ def veda_tile_layout_stats(plan: Plan, x: torch.Tensor, x_tiled: Optional[torch.
     want_tiles=False: descriptors (and masks) only, x_tiled is returned as None."""
     dev = x.device
     if x_tiled is None and want_tiles:
-        x_tiled = torch.empty((plan.batch, plan.total_tiles, 64 * plan.head_dim), dtype=x.dtype, device=dev)
+        x_tiled = torch.empty((plan.batch, plan.total_tiles, plan.tile_tokens * plan.head_dim), dtype=x.dtype,
+                              device=dev)
     if want_mask and valid_mask is None:
-        valid_mask = torch.empty(plan.total_tiles, dtype=torch.int64, device=dev)
+        valid_mask = torch.empty(plan.total_tiles * plan.mask_words, dtype=torch.int64, device=dev)
     if want_mask and valid_cnt is None:
         valid_cnt = torch.empty(plan.total_tiles, dtype=torch.int32, device=dev)
     if stats is None:
@@ -455,7 +456,7 @@ def veda_attention(plan: Plan, q, k, v, phi_q: Mlp, phi_k: Mlp, k_per_head, scor
     """The whole path in call order: layout x3 -> score -> select -> sparse attention.
     fused=True takes the descriptors during the Q and K gathers (veda_tile_layout_stats +
     veda_tile_score_stats); one_call=True runs stages 2 and 3 through veda_tile_score_select*,
-    which never writes the score matrix; from_tokens=True (with fused, bf16, 64-token tiles) writes no
+    which never writes the score matrix; from_tokens=True (with fused, bf16) writes no
     tiled copy of Q and K: the gathers only take descriptors and masks, and the attention kernel
     gathers the rows of both from token order.  The results are bit-identical whichever way.
     `buffers` (optional dict) is filled on the first call and reused afterwards so that a

@@ -494,15 +494,17 @@ def test_score_select_in_one_call_other_shapes():
         assert e.value.status == veda.VEDA_ERR_WORKSPACE
 
 
-def test_whole_path_wrapper_routes_agree():
+@pytest.mark.parametrize("tile_tokens", [64, 128])
+def test_whole_path_wrapper_routes_agree(tile_tokens):
     # veda_attention in its six routes (descriptors from the gather or not, stages 2+3 in one call
     # or two, Q and K tiled or read from token order): same lists, same output bits; buffers of a
-    # first call are reused by a second
+    # first call are reused by a second.  With 128-token tiles the ragged grid leaves half tiles
+    # without a single real token (8x4x4 on 9 frames, 1x8x16 on 18 columns).
     wl = wlm.custom_workload("routes", 3, 128, "bf16", (9, 18, 18), True, (25, 100), seed=12)
     dev = torch.device("cuda:0")
-    shapes = wlm.tile_shapes(wl)
+    shapes = wlm.tile_shapes(wl) if tile_tokens == 64 else np.asarray([(8, 4, 4), (2, 8, 8), (1, 8, 16)], np.int32)
     q, k, v = wlm.make_qkv(wl, dev)
-    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=tile_tokens)
     kph = wlm.keep_budget(wl, None, shapes)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
@@ -518,9 +520,19 @@ def test_whole_path_wrapper_routes_agree():
                                       buffers=bufs, fused=fused, one_call=one_call, from_tokens=from_tokens)
         torch.cuda.synchronize()
         assert out2.data_ptr() == out.data_ptr() and torch.equal(out2.view(torch.int16), first.view(torch.int16))
-        outs.append((out2.view(torch.int16).clone(), bufs["ci"].clone()))
-    for o, ci in outs[1:]:
+        outs.append((out2.view(torch.int16).clone(), bufs["ci"].clone(), bufs["vm"].clone(), bufs["vc"].clone(),
+                     None if bufs.get("zq") is None or not fused else bufs["zq"].view(torch.int32).clone()))
+    for o, ci, vm, vc, _ in outs[1:]:
         assert torch.equal(o, outs[0][0]) and torch.equal(ci, outs[0][1])
+        assert torch.equal(vm, outs[0][2]) and torch.equal(vc, outs[0][3])     # masks and counts, from either gather
+    # the descriptors of the gathers that write the tiles and of those that do not are the same bits
+    assert torch.equal(outs[2][4], outs[4][4])
+    # and they are the oracle's TripPool (Eq. 4) of every head
+    zq = outs[2][4].view(torch.float32).cpu().numpy()
+    for h in range(wl.heads):
+        ref = vo.trippool(hz.to_f32_numpy(q[0, h]), wl.grid, tuple(int(x) for x in shapes[h]))
+        got = zq[0, plan.tile_offset[h]:plan.tile_offset[h] + plan.tiles[h]]
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (tile_tokens, h)
 
 
 def test_whole_path_replayed_from_a_hip_graph():
