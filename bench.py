@@ -28,10 +28,43 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBPS = 8000.0
 
-# Bytes per sparse-attention launch crossing the L2 -> memory-fabric port, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size
-# (profiles/sparse_attn_waver12b_720p_241f_pmc.txt), keyed by workload; None where not measured.
-MEASURED_TRAFFIC_BYTES = {"waver12b_720p_241f": 2.0 * 85323922 * 1024 + 1317600 * 1024}
+# roofline.traffic comes from the tracked counter summaries under profiles/: a line
+#   traffic_record kernel=<name> workload=<name> tile_tokens=<B> keep=<num>/<den> route=<q>,<k> source_sha=<12 hex>
+#                  fetch_kib=<FETCH_SIZE> fetch_scale=<x> write_kib=<WRITE_SIZE> write_scale=<x>
+# gives the rocprofv3 --pmc readings (KiB per dispatch) and the factors that calibrate them against a
+# copy kernel of known size.  A record is used only if it names the workload, tile size, keep
+# fraction and Q/K route of this run AND the hash of the attention kernel's sources as they are now;
+# otherwise traffic is null and traffic_source says why.
+KERNEL_SOURCES = ("attn_pair.hip", "attn_common.h", "attn.hip", "veda_internal.h", "geometry.h")
+
+
+def kernel_source_sha() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        h.update((ROOT / "paper_2605_30325_amd" / "csrc" / name).read_bytes())
+    return h.hexdigest()[:12]
+
+
+def measured_traffic(kernel: str, workload: str, tile_tokens: int, keep, route_qk: str):
+    """(bytes per launch or None, where it came from / why there is none)."""
+    sha = kernel_source_sha()
+    want = {"kernel": kernel, "workload": workload, "tile_tokens": str(tile_tokens), "keep": f"{keep[0]}/{keep[1]}",
+            "route": route_qk}
+    stale = None
+    for path in sorted((ROOT / "profiles").glob("*.txt")):
+        for line in path.read_text().splitlines():
+            if not line.startswith("traffic_record "):
+                continue
+            rec = dict(kv.split("=", 1) for kv in line.split()[1:])
+            if any(rec.get(k) != v for k, v in want.items()):
+                continue
+            if rec.get("source_sha") != sha:
+                stale = f"profiles/{path.name} has a record for this run, taken from other kernel sources ({rec.get('source_sha')}, now {sha})"
+                continue
+            nbytes = (float(rec["fetch_kib"]) * float(rec["fetch_scale"]) + float(rec["write_kib"]) * float(rec["write_scale"])) * 1024.0
+            return nbytes, f"profiles/{path.name} (source_sha {sha})"
+    return None, stale or f"no counter record under profiles/ for {want} at source_sha {sha}"
 
 
 def parse():
@@ -64,6 +97,9 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (the per-stage times and the "
                          "roofline then come from eager steps run after the timed region)")
+    ap.add_argument("--exact-logit-scale", action="store_true",
+                    help="VEDA_OPT_EXACT_LOGIT_SCALE: Q scaled by a power of two only, the rest of softmax_scale*log2(e) "
+                         "applied to the logits in fp32 (error independent of the logits' size, about 4 % more time)")
     ap.add_argument("--unfused", action="store_true",
                     help="stage 2 re-reads the tiled Q and K for its descriptors (veda_tile_layout + veda_tile_score) "
                          "instead of taking them during the gathers")
@@ -169,6 +205,8 @@ def main():
         shapes = shapes * np.asarray([2, 1, 1], np.int32)
     q, k, v = wlm.make_qkv(wl, dev)
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=B)
+    if args.exact_logit_scale:
+        plan.set_option(veda.VEDA_OPT_EXACT_LOGIT_SCALE, 1)
     kph = wlm.keep_budget(wl, keep, shapes)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
@@ -202,6 +240,12 @@ def main():
         bytes_layout -= slots * d * es   # the tiled copy of Q is not written
     if k_from_tokens:
         bytes_layout -= slots * d * es   # nor that of K
+    route = {"stage1": "gather + reread for descriptors" if args.unfused else "descriptors during the gather",
+             "stages23": "two calls, score matrix in HBM" if args.two_stage else "one call, no score matrix",
+             "q": "token order" if q_from_tokens else "tiled copy", "k": "token order" if k_from_tokens else "tiled copy",
+             "logit_scale": "exact (power of two into Q)" if args.exact_logit_scale else "default (Q pre-scaled, rounded once)"}
+    route_qk = ("tokens" if q_from_tokens else "tiled") + "," + ("tokens" if k_from_tokens else "tiled") + (
+        ",exact" if args.exact_logit_scale else "")
     bufs = {}
 
     def step(events=None):
@@ -289,6 +333,8 @@ def main():
         attn_each[len(attn_each) // 2 - 1] + attn_each[len(attn_each) // 2])
     kept_tflops = kept_flops / (attn_ms * 1e-3) / 1e12
 
+    kernel_name = "sparse_attn_bf16_pair_kernel" if wl.dtype == "bf16" else "sparse_attn_f32_kernel"
+    traffic, traffic_source = measured_traffic(kernel_name, wl.name, B, keep or wl.keep, route_qk)
     result = {
         "metric": "dense_equiv_tflops_whole_path" if not args.attn_only else "dense_equiv_tflops_attn_only",
         "value": dense_flops / (ms_per_step * 1e-3) / 1e12,
@@ -298,25 +344,26 @@ def main():
         "dtype": wl.dtype, "data": "synthetic", "launch": "hip_graph" if args.graph else "eager",
         "config": {"workload": wl.name, "grid": list(wl.grid), "tokens": N, "heads": heads, "head_dim": d,
                    "tile_tokens": B, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
-                   "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch)},
+                   "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch), "route": route},
         "attn_ms_per_call": attn_ms, "attn_ms_median": attn_ms_median,
         "attn_ms_min": attn_each[0], "attn_ms_max": attn_each[-1],
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
         "attn_kept_tflops": kept_tflops,
         "stage_ms": stage_ms,
-        "roofline": {"kernel": "sparse_attn_bf16_pair_kernel" if wl.dtype == "bf16" else "sparse_attn_f32_kernel",
+        "roofline": {"kernel": kernel_name,
                      "bound": "mfma" if wl.dtype == "bf16" else "alu",
                      "achieved": kept_tflops,
                      "peak": PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS,
                      "unit": "TFLOP/s",
                      "frac": kept_tflops / (PEAK_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_F32_VALU_TFLOPS),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if B == 64 else None,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "flops_per_launch": kept_flops, "kv_tile_bytes_per_launch": bytes_attn_kv},
-        # clock the driver reported during the timed steps, and the rate against the matrix peak
-        # at that clock (256 CUs x 4096 FLOP per clock)
-        "sclk_mhz": sclk,
-        "mfma_util_at_observed_clock": (kept_tflops * 1e12 / (sclk["mean"] * 1e6 * 256 * 4096)
-                                        if sclk and wl.dtype == "bf16" else None),
+        # Diagnostics only, never compared with the target (roofline.frac against the nominal peak
+        # is): the clock the driver reported during the timed steps and the share of the matrix
+        # pipes' cycles AT THAT CLOCK that the kept-tile FLOPs fill (256 CUs x 4096 FLOP per clock)
+        "diagnostics": {"sclk_mhz": sclk,
+                        "matrix_pipe_busy_at_observed_clock": (kept_tflops * 1e12 / (sclk["mean"] * 1e6 * 256 * 4096)
+                                                               if sclk and wl.dtype == "bf16" else None)},
     }
     if not args.attn_only:
         stage_bytes = {"layout": bytes_layout, "score": bytes_score, "select": bytes_select,

@@ -11,7 +11,9 @@
  *    is the default stream) and returns without synchronising.
  *  - Arguments are checked on the host before anything is launched; a failed check returns
  *    an error code and launches nothing.  HIP launch failures map to VEDA_ERR_HIP.
- *  - No atomics, no data-dependent scheduling of arithmetic: equal inputs give equal bytes.
+ *  - No data-dependent scheduling of arithmetic and no floating-point atomics: equal inputs give
+ *    equal bytes.  (The only atomics are the integer adds of veda_tile_recall's hit counters,
+ *    whose sum does not depend on their order.)
  *  - Tokens are the raster flattening n = (t*H + h)*W + w of a latent grid (T,H,W)
  *    (Sec. 3.1).  A head's tile shape pi = (p_t,p_h,p_w) with p_t*p_h*p_w = B (Eq. 7)
  *    partitions the grid, each axis padded up to a multiple of the tile extent.  Tile i and
@@ -20,7 +22,8 @@
  *    so temporal neighbours inside a tile are p_h*p_w slots apart (App. A.5).  Heads may
  *    have different shapes, hence different tile counts N_T[h]; tiles of all heads are
  *    concatenated head by head ("global tile index" g = tile_off[h] + i).
- *  - Only B = 64, head_dim in {64,128}, dtype in {f32,bf16}, heads <= 128 are supported.
+ *  - Supported: B = 64 (f32 or bf16) and B = 128 (bf16 only; see veda_problem), head_dim in
+ *    {64,128}, heads <= 128.
  */
 #ifndef VEDA_H_
 #define VEDA_H_
@@ -92,6 +95,12 @@ typedef struct {
 veda_status veda_plan_create(const veda_problem* problem, veda_plan** out);
 void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
 
+/* Options of a plan; they take effect for the stage calls made after the setter returns.
+ * VEDA_OPT_EXACT_LOGIT_SCALE (0 = off, the default; 1 = on), bf16 stage 4 (Eq. 2): see
+ * veda_sparse_attn_fwd. */
+typedef enum { VEDA_OPT_EXACT_LOGIT_SCALE = 0 } veda_option;
+veda_status veda_plan_set_option(veda_plan*, veda_option option, int32_t value);
+
 int32_t veda_plan_tiles(const veda_plan*, int32_t head);      /* N_T[h]; -1 on bad args        */
 int64_t veda_plan_tile_offset(const veda_plan*, int32_t head);/* tile_off[h] = sum_{h'<h} N_T  */
 int64_t veda_plan_score_offset(const veda_plan*, int32_t head);/* sum_{h'<h} N_T[h']^2          */
@@ -100,6 +109,14 @@ int64_t veda_plan_score_elems(const veda_plan*);              /* sum_h N_T[h]^2 
 /* Bytes of scratch veda_tile_score needs for the given projections (descriptors, hidden layers
  * and latents). */
 size_t veda_plan_workspace_bytes(const veda_plan*, const veda_mlp* phi_q, const veda_mlp* phi_k);
+/* Where veda_tile_score leaves its intermediates in the workspace, as offsets in floats from its
+ * start; each array is [batch*total_tiles] rows: TripPool descriptors z = [Avg|Max|Min] of Q and
+ * K (3*head_dim floats per row, Eq. 4) and latents phi_q(z_q), phi_k(z_k) (out_dim floats per
+ * row, Eq. 5).  veda_tile_score_stats leaves only the latents, at latent_q - 2*stats and
+ * latent_k - 2*stats, i.e. at the start of its workspace (stats = batch*total_tiles*3*head_dim). */
+typedef struct { int64_t stats_q, stats_k, latent_q, latent_k; } veda_workspace_layout;
+veda_status veda_plan_workspace_layout(const veda_plan*, const veda_mlp* phi_q, const veda_mlp* phi_k,
+                                       veda_workspace_layout* out);
 
 /* ---- stage 1: head-aware 3D tiling (Sec. 4.2; Alg. 1 "Tiling"; Alg. 2 "Tile") ----------- */
 /* x        device, token order, strides sx, plan dtype.
@@ -117,9 +134,16 @@ veda_status veda_tile_layout(const veda_plan*, const void* x, veda_strides sx, v
  *          z = [Avg|Max|Min] over the tile's real tokens, per channel.
  * Arithmetic is fp32 with a fixed order (slot-ascending add chain for Avg; one fma chain per
  * output in ascending input index, started from the bias, for phi; one fma chain from +0 in
- * ascending latent index, then one multiply by `scale`, for the score), so the scores are
- * reproducible to the bit on any conforming fp32 implementation.
- * workspace device scratch of at least veda_plan_workspace_bytes(); contents undefined after. */
+ * ascending latent index, then one multiply by `scale`, for the score), so any conforming fp32
+ * implementation of that order gives the same bits.  On gfx950 the projection chains and the
+ * chains of veda_tile_score's score matrix are issued as v_mfma_f32_32x32x2_f32 over ascending
+ * index pairs: that this instruction applies its two terms one after the other, each rounded as
+ * an fma, denormals kept, is a property measured on gfx950 (and pinned by the parity tests), not
+ * one its ISA manual states; the fused route (veda_tile_score_select*) forms its scores with
+ * plain fmaf chains on the vector units.
+ * workspace device scratch of at least veda_plan_workspace_bytes().  After the call it holds the
+ * stage's intermediates at the float offsets veda_plan_workspace_layout() reports (descriptors
+ * and latents, one row per (batch, global tile)); the rest is undefined. */
 veda_status veda_tile_score(const veda_plan*, const void* q_tiled, const void* k_tiled,
                             const uint64_t* valid_mask, const veda_mlp* phi_q, const veda_mlp* phi_k,
                             float scale, float* scores, void* workspace, size_t workspace_bytes,
@@ -215,8 +239,16 @@ veda_status veda_tile_score_select_stats_noalloc(const veda_plan*, const float* 
  *          query tile i, O[u] = softmax over the real tokens of the kept key tiles of
  *          (q_u.k_v * softmax_scale) applied to V.  Padded query slots write nothing.
  * lse      optional device fp32 [batch][heads][N]: natural-log sum of exp of the kept logits.
- * bf16: Q K^T and P V run on bf16 MFMA with fp32 accumulation, softmax in fp32; Q is scaled
- * by softmax_scale*log2(e) and rounded to bf16 once, P is rounded to bf16 before P V.
+ * bf16: Q K^T and P V run on bf16 MFMA with fp32 accumulation, softmax in fp32, P is rounded to
+ * bf16 before P V.  By default Q is multiplied by softmax_scale*log2(e) and rounded to bf16 once:
+ * an error in every logit of about 2^-9 of its size, so the output error grows with the logits
+ * (measured against the double-precision definition on N(0,1) keys and values: max-abs 5e-3 /
+ * mean-abs 4e-4 with logits q.k*softmax_scale of standard deviation 1, 1.4e-2 / 7e-4 at 2,
+ * 2.4e-2 / 1.6e-3 at 4, 5e-2 / 2e-3 at 6; lse 2e-3 ... 5e-2) and passes max-abs 2e-2 beyond a
+ * standard deviation of about 3.  With VEDA_OPT_EXACT_LOGIT_SCALE Q is multiplied by the power
+ * of two nearest below that factor (exact in bf16) and the logits by the remaining factor in fp32
+ * on their way into the exponential: the error no longer depends on the logits' size (max-abs
+ * <= 1.7e-2, mean-abs <= 1e-3, lse 1e-5 up to a standard deviation of 16) at about 4 % more time.
  * f32: fp32 arithmetic throughout. */
 veda_status veda_sparse_attn_fwd(const veda_plan*, const void* q_tiled, const void* k_tiled,
                                  const void* v_tiled, const uint64_t* valid_mask,
@@ -231,8 +263,9 @@ veda_status veda_sparse_attn_fwd_q_tokens(const veda_plan*, const void* q, veda_
                                           const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,
                                           void* out, veda_strides so, float* lse, void* stream);
 /* And with K from token order as well (k, strides sk; bf16 plans; tokens * sk.n * 2 bytes must stay
- * below 4 GiB): every kept key tile is gathered row by row on its way into the compute unit, so
- * only V needs a tiled copy.  Bit-identical results again. */
+ * below 4 GiB - 4 KiB): every kept key tile is gathered row by row on its way into the compute unit, so
+ * only V needs a tiled copy.  Bit-identical results again.  Both token-order entry points take
+ * either tile size (with B = 128 the kernel gathers the two 64-slot halves of a tile). */
 veda_status veda_sparse_attn_fwd_qk_tokens(const veda_plan*, const void* q, veda_strides sq, const void* k,
                                            veda_strides sk, const void* v_tiled, const uint64_t* valid_mask,
                                            const int32_t* row_ptr, const int32_t* col_idx, float softmax_scale,

@@ -150,10 +150,16 @@ static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const v
     a.tokens = pl->tokens();
     a.n_heads = pl->prob.heads; a.T = pl->prob.T; a.H = pl->prob.H; a.W = pl->prob.W;
     a.scale_log2 = softmax_scale * kLog2e;
+    {
+        int ex = 0;
+        const float mant = frexpf(a.scale_log2, &ex);   // scale_log2 = mant * 2^ex, 0.5 <= mant < 1
+        a.scale_pow2 = ldexpf(1.0f, ex - 1);
+        a.scale_resid = 2.0f * mant;
+    }
     hipStream_t s = (hipStream_t)stream;
     if (pl->prob.dtype == VEDA_BF16) {
         a.xcd_cum = ip->d_xcd_cum_pair;
-        return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, s);
+        return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, pl->exact_logit_scale, s);
     }
     a.xcd_cum = pl->d_xcd_cum;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_tiles), (unsigned)pl->prob.batch), block(256);

@@ -34,6 +34,11 @@ struct AttnArgs {
     int64_t tokens;
     int n_heads, T, H, W;
     float scale_log2;          // softmax_scale * log2(e)
+    // scale_log2 = scale_pow2 * scale_resid, scale_pow2 a power of two and 1 <= scale_resid < 2: with the
+    // plan's exact-logit-scale option the bf16 kernel multiplies Q by scale_pow2 (exact in bf16) and the
+    // logits by scale_resid on their way into the exponential, so no rounding of Q comes between the
+    // inputs and the products; without it Q is multiplied by scale_log2 and rounded to bf16 once
+    float scale_pow2, scale_resid;
 };
 
 // Workgroups are dealt round-robin to the 8 dies (XCDs), each with its own L2, all sharing
@@ -142,6 +147,7 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 
 // Launches the query-tile-pair bf16 kernel (attn_pair.hip) on plan pl's geometry; a.xcd_cum must be
 // its pair table.  grouped: pl is the inner plan of 128-token tiles and the CSR counts whole tiles.
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s);
+// exact: the power-of-two / residual split of the logit scale (AttnArgs::scale_pow2, scale_resid).
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, hipStream_t s);
 
 }  // namespace veda

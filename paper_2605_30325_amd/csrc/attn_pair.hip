@@ -51,6 +51,7 @@ template <int D> struct PairState {
     f32x16 start;        // -ref in every register: the C operand of the first MFMA of an S^T block
     bf16x8 qf[D / 16];
     float ref, l_run;
+    float resid;         // logits are held divided by this factor (see AttnArgs::scale_resid)
     bool started;
 };
 
@@ -84,7 +85,7 @@ struct PairAddr {
 //     forming those exponentials again.
 constexpr int kSideCalls = 4;
 
-template <int D> struct PairStep {
+template <int D, bool kExact> struct PairStep {
     static constexpr int G = D / 16, NB = D / 32, kAhead = 6;
     static constexpr int kRowB = D * 2;
     static constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
@@ -127,8 +128,9 @@ template <int D> struct PairStep {
         typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 #define VEDA_EXP(kk, e)                                                                         \
     do {                                                                                        \
-        const float p0_ = __builtin_amdgcn_exp2f(s[(kk) >> 1][8 * ((kk) & 1) + (e)]);           \
-        const float p1_ = __builtin_amdgcn_exp2f(s[(kk) >> 1][8 * ((kk) & 1) + (e) + 1]);       \
+        const float x0_ = s[(kk) >> 1][8 * ((kk) & 1) + (e)], x1_ = s[(kk) >> 1][8 * ((kk) & 1) + (e) + 1]; \
+        const float p0_ = __builtin_amdgcn_exp2f(kExact ? x0_ * st.resid : x0_);                \
+        const float p1_ = __builtin_amdgcn_exp2f(kExact ? x1_ * st.resid : x1_);                \
         const bf16x2 pr_ = {(__bf16)p0_, (__bf16)p1_};                                          \
         psum += p0_;                                                                            \
         psum += p1_;                                                                            \
@@ -158,7 +160,7 @@ template <int D> struct PairStep {
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
         // this lane's half of the row maximum is enough to see whether ANY row of the wave outgrew its reference
-        if (__builtin_expect(vm != ~0ull || !st.started || __any(mx > kPairSlack), 0)) {
+        if (__builtin_expect(vm != ~0ull || !st.started || __any((kExact ? mx * st.resid : mx) > kPairSlack), 0)) {
             // The empty asm keeps this a real branch: if-converted into the main block its ~150 vector
             // ops would run on every step.
             asm volatile("" ::: "memory");
@@ -178,12 +180,12 @@ template <int D> struct PairStep {
                 }
             }
             mx = max_with_other_half(mx);   // row maximum relative to the reference
-            if (!st.started || __any(mx > kPairSlack)) {
+            if (!st.started || __any((kExact ? mx * st.resid : mx) > kPairSlack)) {
                 // Move the reference of every row whose maximum is above it (first step: to the
                 // maximum itself, up or down).
                 float delta = st.started ? fmaxf(mx, 0.0f) : mx;
                 delta = delta == -INFINITY ? 0.0f : delta;
-                const float alpha = st.started ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // O = l = 0 before
+                const float alpha = st.started ? __builtin_amdgcn_exp2f(kExact ? -delta * st.resid : -delta) : 1.0f;   // O = l = 0 before
                 st.ref += delta;
                 st.l_run *= alpha;
 #pragma unroll
@@ -258,7 +260,7 @@ __device__ __forceinline__ void finish_pair(const PairState<D>& st, const AttnAr
                 for (int t = 0; t < 4; ++t) pk[t] = (__bf16)(st.o[nb][4 * j + t] * inv);
                 *reinterpret_cast<bf16x4*>(orow + d0 * 2) = pk;
             }
-        if (hh == 0) lse_s[which * kTile + 32 * r + lq] = (st.ref + __log2f(l_all)) * kLn2;
+        if (hh == 0) lse_s[which * kTile + 32 * r + lq] = (st.ref * st.resid + __log2f(l_all)) * kLn2;
     }
     __syncthreads();
     char* ob = a.out + b * a.so_b + head * a.so_h;
@@ -290,7 +292,7 @@ struct MergedStep {
 // kTokK: K is read from token order (a.k_tok) instead of the tiled tensor: a key tile's rows
 // are found at first-token + (lt*H + lh)*W + lw; the rows of padded slots are fetched from slot 0
 // instead (any finite or non-finite value will do: their logits are overwritten with -inf).
-template <int D, bool kGrouped, bool kTokK>
+template <int D, bool kGrouped, bool kTokK, bool kExact>
 __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs a) {
     constexpr int kRowB = D * 2;                 // bytes of one K row
     constexpr int kKBytes = kTile * kRowB;       // K tile
@@ -349,7 +351,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
         for (int t = 0; t < G; ++t) {
             const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + 32 * t);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.qf[t][e] = real ? (__bf16)((float)raw[e] * a.scale_log2) : (__bf16)0.0f;
+            for (int e = 0; e < 8; ++e) st.qf[t][e] = real ? (__bf16)((float)raw[e] * (kExact ? a.scale_pow2 : a.scale_log2)) : (__bf16)0.0f;
         }
     }
 #pragma unroll
@@ -359,6 +361,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.start[i] = 0.0f;
     st.ref = st.l_run = 0.0f;
+    st.resid = kExact ? a.scale_resid : 1.0f;
     st.started = false;
 
     // global -> LDS copy plan.  One wave instruction fills 1 KB of LDS, lane i at byte 16*i, so
@@ -489,7 +492,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     do {                                                                                                 \
         int todo = 1;                                                                                    \
         if (__builtin_expect((e0.fl & my_bit) != 0, 1)) {                                                \
-            PairStep<D> w;                                                                               \
+            PairStep<D, kExact> w;                                                                            \
             w.begin(fa, (uint32_t)((P) * kSlot));                                                        \
             w.template block0<0>(st);                                                                    \
             if (e1.fl) load_tile(e1, (P) ^ 1, 0);                                                        \
@@ -525,12 +528,15 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     finish_pair<D>(st, a, hg, smem, head, qiA, qiB, hasB, b, tid, which, r, lq, hh);
 }
 
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, hipStream_t s) {
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, hipStream_t s) {
     const int d = pl->prob.head_dim;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
     const size_t smem = (size_t)2 * 2 * kTile * d * 2;   // two slots of (K tile + V^T tile)
-#define VEDA_LAUNCH_PAIR(DD, GG, KK) \
-    hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK>), grid, block, smem, s, a)
+#define VEDA_LAUNCH_PAIR(DD, GG, KK)                                                                     \
+    do {                                                                                                 \
+        if (exact) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK, true>), grid, block, smem, s, a);   \
+        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK, false>), grid, block, smem, s, a);        \
+    } while (0)
     const int variant = (d == 128 ? 4 : 0) | (grouped ? 2 : 0) | (a.k_tok ? 1 : 0);
     switch (variant) {
         case 0: VEDA_LAUNCH_PAIR(64, false, false); break;

@@ -209,6 +209,17 @@ void veda_plan_destroy(veda_plan* pl) {
     delete pl;
 }
 
+veda_status veda_plan_set_option(veda_plan* pl, veda_option option, int32_t value) {
+    if (!pl) return VEDA_ERR_INVALID_ARG;
+    switch (option) {
+        case VEDA_OPT_EXACT_LOGIT_SCALE:
+            if (value != 0 && value != 1) return VEDA_ERR_INVALID_ARG;
+            pl->exact_logit_scale = value != 0;
+            return VEDA_OK;
+    }
+    return VEDA_ERR_INVALID_ARG;
+}
+
 int32_t veda_plan_tiles(const veda_plan* pl, int32_t head) {
     if (!pl || head < 0 || head >= pl->prob.heads) return -1;
     return pl->heads[head].n_tiles;

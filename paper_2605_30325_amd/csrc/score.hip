@@ -474,6 +474,17 @@ static veda_status project_and_score(const veda_plan* pl, const veda_mlp* phi_q,
 
 }  // namespace veda
 
+extern "C" veda_status veda_plan_workspace_layout(const veda_plan* pl, const veda_mlp* phi_q, const veda_mlp* phi_k,
+                                                  veda_workspace_layout* out) {
+    if (!pl || !phi_q || !phi_k || !out || phi_q->out_dim != phi_k->out_dim) return VEDA_ERR_INVALID_ARG;
+    const int64_t rows = pl->total_tiles * pl->prob.batch, d = pl->prob.head_dim, dp = phi_q->out_dim;
+    out->stats_q = 0;                       // the order veda_tile_score carves its workspace in
+    out->stats_k = rows * 3 * d;
+    out->latent_q = 2 * rows * 3 * d;
+    out->latent_k = 2 * rows * 3 * d + rows * dp;
+    return VEDA_OK;
+}
+
 extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled, const void* k_tiled,
                                        const uint64_t* valid_mask, const veda_mlp* phi_q,
                                        const veda_mlp* phi_k, float scale, float* scores, void* workspace,
@@ -487,12 +498,14 @@ extern "C" veda_status veda_tile_score(const veda_plan* pl, const void* q_tiled,
     if (!aligned16(q_tiled) || !aligned16(k_tiled) || !aligned16(workspace)) return VEDA_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < veda_plan_workspace_bytes(pl, phi_q, phi_k)) return VEDA_ERR_WORKSPACE;
 
-    const int d = pl->prob.head_dim, dp = phi_q->out_dim;
+    const int dp = phi_q->out_dim;
     const int64_t total = pl->total_tiles, rows = total * pl->prob.batch;
-    float* zq = (float*)workspace;
-    float* zk = zq + rows * 3 * d;
-    float* yq = zk + rows * 3 * d;
-    float* yk = yq + rows * dp;
+    veda_workspace_layout lay;
+    (void)veda_plan_workspace_layout(pl, phi_q, phi_k, &lay);
+    float* zq = (float*)workspace + lay.stats_q;
+    float* zk = (float*)workspace + lay.stats_k;
+    float* yq = (float*)workspace + lay.latent_q;
+    float* yk = (float*)workspace + lay.latent_k;
     float* hq = yk + rows * dp;               // the plan's workspace size has room for both hidden layers
     float* hk = hq + rows * (phi_q->hidden > 0 ? phi_q->hidden : 0);
     hipStream_t s = (hipStream_t)stream;

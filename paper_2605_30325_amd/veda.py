@@ -21,11 +21,12 @@ VEDA_OK, VEDA_ERR_INVALID_ARG, VEDA_ERR_UNSUPPORTED, VEDA_ERR_WORKSPACE, VEDA_ER
 VEDA_F32, VEDA_BF16 = 0, 1
 VEDA_ACT_IDENTITY, VEDA_ACT_RELU = 0, 1
 VEDA_TOKEN_MAJOR, VEDA_CHANNEL_MAJOR = 0, 1
+VEDA_OPT_EXACT_LOGIT_SCALE = 0
 
 EXPORTS = (
-    "veda_plan_create", "veda_plan_destroy", "veda_plan_tiles", "veda_plan_tile_offset",
+    "veda_plan_create", "veda_plan_destroy", "veda_plan_set_option", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
-    "veda_plan_workspace_bytes", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
+    "veda_plan_workspace_bytes", "veda_plan_workspace_layout", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
     "veda_tile_score_select", "veda_tile_score_select_stats", "veda_tile_score_select_stats_noalloc",
     "veda_sparse_attn_fwd", "veda_sparse_attn_fwd_q_tokens",
@@ -55,6 +56,10 @@ class veda_mlp(C.Structure):
                 ("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
 
 
+class veda_workspace_layout(C.Structure):
+    _fields_ = [("stats_q", C.c_int64), ("stats_k", C.c_int64), ("latent_q", C.c_int64), ("latent_k", C.c_int64)]
+
+
 _lib = None
 
 
@@ -71,6 +76,8 @@ def load():
     L.veda_plan_create.restype = C.c_int
     L.veda_plan_destroy.argtypes = [vp]
     L.veda_plan_destroy.restype = None
+    L.veda_plan_set_option.argtypes = [vp, C.c_int, i32]
+    L.veda_plan_set_option.restype = C.c_int
     L.veda_plan_tiles.argtypes = [vp, i32]
     L.veda_plan_tiles.restype = i32
     for name in ("veda_plan_tile_offset", "veda_plan_score_offset"):
@@ -81,6 +88,8 @@ def load():
         getattr(L, name).restype = i64
     L.veda_plan_workspace_bytes.argtypes = [vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp)]
     L.veda_plan_workspace_bytes.restype = C.c_size_t
+    L.veda_plan_workspace_layout.argtypes = [vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.POINTER(veda_workspace_layout)]
+    L.veda_plan_workspace_layout.restype = C.c_int
     L.veda_tile_layout.argtypes = [vp, vp, veda_strides, C.c_int, vp, vp, vp, vp]
     L.veda_tile_layout.restype = C.c_int
     L.veda_tile_score.argtypes = [vp, vp, vp, vp, C.POINTER(veda_mlp), C.POINTER(veda_mlp), C.c_float,
@@ -200,8 +209,18 @@ class Plan:
         self.total_tiles = int(L.veda_plan_total_tiles(h))
         self.score_elems = int(L.veda_plan_score_elems(h))
 
+    def set_option(self, option: int, value: int):
+        _check(load().veda_plan_set_option(self.handle, option, int(value)), "veda_plan_set_option")
+
     def workspace_bytes(self, phi_q: Mlp, phi_k: Mlp) -> int:
         return int(load().veda_plan_workspace_bytes(self.handle, C.byref(phi_q.struct()), C.byref(phi_k.struct())))
+
+    def workspace_layout(self, phi_q: Mlp, phi_k: Mlp) -> veda_workspace_layout:
+        """Float offsets of the intermediates veda_tile_score leaves in its workspace."""
+        lay = veda_workspace_layout()
+        _check(load().veda_plan_workspace_layout(self.handle, C.byref(phi_q.struct()), C.byref(phi_k.struct()),
+                                                 C.byref(lay)), "veda_plan_workspace_layout")
+        return lay
 
     def close(self):
         if self.handle is not None:

@@ -48,6 +48,8 @@ class GpuRun:
     bufs: Dict[str, torch.Tensor]
     out: torch.Tensor
     lse: Optional[torch.Tensor]
+    mlp_q: Optional[veda.Mlp] = None      # the device-resident projections the run used
+    mlp_k: Optional[veda.Mlp] = None
 
 
 def score_scale_of(wl: wlm.Workload) -> float:
@@ -77,7 +79,17 @@ def run_gpu_path(wl: wlm.Workload, keep=None, k_per_head=None, want_lse=True, sh
     out, lse = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, rp, ci, softmax_scale, out=out, want_lse=want_lse)
     torch.cuda.synchronize()
     bufs = dict(qt=qt, kt=kt, vt=vt, vm=vm, vc=vc, s=s, ws=ws, rp=rp, ci=ci)
-    return GpuRun(wl, plan, shapes, kph, q, k, v, eq, ek, sscale, softmax_scale, bufs, out, lse)
+    return GpuRun(wl, plan, shapes, kph, q, k, v, eq, ek, sscale, softmax_scale, bufs, out, lse, pq, pk)
+
+
+def score_intermediates(plan: veda.Plan, phi_q: "veda.Mlp", phi_k: "veda.Mlp", workspace: torch.Tensor):
+    """(z_q, z_k, y_q, y_k) as veda_tile_score left them in its workspace, each [batch*total_tiles, width],
+    found through the offsets the library documents (veda_plan_workspace_layout)."""
+    lay = plan.workspace_layout(phi_q, phi_k)
+    ws = workspace.view(torch.float32)
+    rows, d, dp = plan.batch * plan.total_tiles, plan.head_dim, phi_q.out_dim
+    cut = lambda off, width: ws[off: off + rows * width].view(rows, width)
+    return cut(lay.stats_q, 3 * d), cut(lay.stats_k, 3 * d), cut(lay.latent_q, dp), cut(lay.latent_k, dp)
 
 
 def sample_tiles(n_tiles: int, count: int, seed: int) -> np.ndarray:
@@ -117,15 +129,9 @@ def check_head(run: GpuRun, head: int, batch: int = 0, attn_tiles: Optional[int]
     qf, kf, vf = to_f32_numpy(qh), to_f32_numpy(kh), to_f32_numpy(vh)
     zq, zk, yq, yk, s_ref, idx_ref = vo.estimate_and_select(qf, kf, grid, shape, run.phi_q, run.phi_k, head,
                                                             ksel, np.float32(run.score_scale))
-    rows = plan.total_tiles * wl.batch
-    ws = run.bufs["ws"].view(torch.float32)
-    dp = wl.latent_dim
     r0 = batch * plan.total_tiles + toff
-    g_zq = ws[: rows * 3 * d].view(rows, 3 * d)[r0:r0 + nt].cpu().numpy()
-    g_zk = ws[rows * 3 * d: 2 * rows * 3 * d].view(rows, 3 * d)[r0:r0 + nt].cpu().numpy()
-    base = 2 * rows * 3 * d
-    g_yq = ws[base: base + rows * dp].view(rows, dp)[r0:r0 + nt].cpu().numpy()
-    g_yk = ws[base + rows * dp: base + 2 * rows * dp].view(rows, dp)[r0:r0 + nt].cpu().numpy()
+    g_zq, g_zk, g_yq, g_yk = (t[r0:r0 + nt].cpu().numpy()
+                              for t in score_intermediates(plan, run.mlp_q, run.mlp_k, run.bufs["ws"]))
     assert np.array_equal(g_zq.view(np.uint32), zq.view(np.uint32)), f"{tag}: TripPool(Q) not bit-exact"
     assert np.array_equal(g_zk.view(np.uint32), zk.view(np.uint32)), f"{tag}: TripPool(K) not bit-exact"
     assert np.array_equal(g_yq.view(np.uint32), yq.view(np.uint32)), f"{tag}: phi_q not bit-exact"
