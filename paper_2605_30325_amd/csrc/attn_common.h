@@ -150,4 +150,7 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // exact: the power-of-two / residual split of the logit scale (AttnArgs::scale_pow2, scale_resid).
 veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, hipStream_t s);
 
+// The fp32 kernel (attn_f32.hip): same work items (a.xcd_cum must be the plan's pair table), tiled Q, K, V only.
+veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, hipStream_t s);
+
 }  // namespace veda
