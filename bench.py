@@ -100,6 +100,12 @@ def parse():
     ap.add_argument("--exact-logit-scale", action="store_true",
                     help="VEDA_OPT_EXACT_LOGIT_SCALE: Q scaled by a power of two only, the rest of softmax_scale*log2(e) "
                          "applied to the logits in fp32 (error independent of the logits' size, about 4 % more time)")
+    ap.add_argument("--lists", default="selected", choices=("selected", "partner", "head", "first"),
+                    help="diagnostic for --attn-only (the outputs are no longer the method's): the kept lists the attention "
+                         "call walks.  selected: as stages 2+3 chose them; partner: both query tiles of a workgroup get the "
+                         "list of the first of them (every loaded key tile serves both: 0.5 loads per kept pair, own "
+                         "neighbourhood); head: every row of a head gets the list of the head's middle row (the same, and "
+                         "all workgroups walk the same ~k tiles: cache-hot); first: every row keeps tiles 0..k-1")
     ap.add_argument("--unfused", action="store_true",
                     help="stage 2 re-reads the tiled Q and K for its descriptors (veda_tile_layout + veda_tile_score) "
                          "instead of taking them during the gathers")
@@ -142,14 +148,49 @@ def cpu_baseline(wl, shapes, kph, dense_flops, q, k, v, eq, ek, score_scale, sof
     }
 
 
+def altered_lists(kind, plan, shapes, kph, grid, row_ptr, col_idx):
+    """The kept lists of --lists (see its help); partner lists follow the library's pairing rule
+    (partners along the thinnest tile axis with an even tile count, ties to w, then h)."""
+    import numpy as np
+    import torch
+    T, H, W = grid
+    rp = row_ptr.cpu().numpy()
+    out = col_idx.clone()
+    for h in range(plan.heads):
+        n, kk, lo = plan.tiles[h], int(kph[h]), int(rp[plan.tile_offset[h]])
+        lists = col_idx[lo:lo + n * kk].view(n, kk)
+        if kind == "first":
+            new = torch.arange(kk, device=col_idx.device, dtype=col_idx.dtype).repeat(n)
+        elif kind == "head":
+            new = lists[n // 2].repeat(n)
+        else:
+            ext = [int(x) for x in shapes[h]]
+            cnt = [-(-T // ext[0]), -(-H // ext[1]), -(-W // ext[2])]
+            ax, best = -1, 0.0
+            for a in (2, 1, 0):
+                if cnt[a] < 2:
+                    continue
+                alone = 1.0 / cnt[a] if cnt[a] % 2 else 0.0
+                cost = (1.0 - alone) * (0.60 if ext[a] == min(ext) else 0.68) + alone
+                if ax < 0 or cost < best - 1e-12:
+                    ax, best = a, cost
+            idx = np.arange(n).reshape(cnt)
+            lead = np.take(idx, np.arange(cnt[ax]) // 2 * 2, axis=ax).reshape(-1)
+            new = lists[torch.as_tensor(lead, device=col_idx.device)].reshape(-1)
+        out[lo:lo + n * kk] = new
+    return out
+
+
 class ShaderClockSampler(threading.Thread):
-    """Reads the shader clock the driver reports for device 0 (sysfs pp_dpm_sclk, the starred
-    entry) every few milliseconds while the timed steps run: the attention kernel is power-limited,
-    so the clock it is held at belongs next to its rate.  Yields nothing if the file is missing."""
+    """Reads the shader clock (sysfs pp_dpm_sclk, the starred entry) and the board power (hwmon
+    power1_input, with its cap) the driver reports for device 0 every few milliseconds while the timed
+    steps run: the attention kernel is power-limited, so the clock it is held at and the power drawn
+    belong next to its rate.  Yields nothing for a file that is missing."""
 
     def __init__(self, period_s: float = 0.003):
         super().__init__(daemon=True)
         self.period, self.samples, self.stop_flag, self.path = period_s, [], threading.Event(), None
+        self.power_path, self.power, self.power_cap = None, [], None
         try:
             import glob
             import torch
@@ -158,6 +199,11 @@ class ShaderClockSampler(threading.Thread):
             for dev in glob.glob("/sys/class/drm/card*/device"):
                 if os.path.realpath(dev).split("/")[-1].startswith(want) and os.path.exists(dev + "/pp_dpm_sclk"):
                     self.path = dev + "/pp_dpm_sclk"
+                    for hw in glob.glob(dev + "/hwmon/hwmon*/power1_input"):
+                        self.power_path = hw
+                        cap = hw.replace("power1_input", "power1_cap")
+                        if os.path.exists(cap):
+                            self.power_cap = int(open(cap).read()) / 1e6
         except Exception:
             self.path = None
 
@@ -170,7 +216,9 @@ class ShaderClockSampler(threading.Thread):
                 m = pat.search(open(self.path).read())
                 if m:
                     self.samples.append(int(m.group(1)))
-            except OSError:
+                if self.power_path:
+                    self.power.append(int(open(self.power_path).read()) / 1e6)
+            except (OSError, ValueError):
                 return
             time.sleep(self.period)
 
@@ -180,7 +228,11 @@ class ShaderClockSampler(threading.Thread):
         if not self.samples:
             return None
         a = self.samples
-        return {"mean": sum(a) / len(a), "min": float(min(a)), "max": float(max(a)), "samples": len(a)}
+        out = {"mean": sum(a) / len(a), "min": float(min(a)), "max": float(max(a)), "samples": len(a)}
+        if self.power:   # the driver's reading is a moving average: the later samples are the steady state
+            tail = self.power[len(self.power) // 2:]
+            out["board_power_w"] = {"mean_second_half": sum(tail) / len(tail), "max": max(self.power), "cap": self.power_cap}
+        return out
 
 
 def main():
@@ -296,6 +348,12 @@ def main():
 
     step()
     torch.cuda.synchronize()
+    if args.lists != "selected":
+        if not args.attn_only or B != 64:
+            print("bench.py: --lists is a diagnostic of the attention call alone: use it with --attn-only, 64-token tiles",
+                  file=sys.stderr)
+            sys.exit(2)
+        bufs["ci"] = altered_lists(args.lists, plan, shapes, kph, wl.grid, bufs["rp"], bufs["ci"])
     run = attn_only if args.attn_only else step
     eager = run
     if args.graph:   # the stage calls only enqueue kernels: one step replayed as a single graph launch
@@ -344,7 +402,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic", "launch": "hip_graph" if args.graph else "eager",
         "config": {"workload": wl.name, "grid": list(wl.grid), "tokens": N, "heads": heads, "head_dim": d,
                    "tile_tokens": B, "keep": list(keep or wl.keep), "kept_tile_pairs": pairs,
-                   "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch), "route": route},
+                   "sparsity": 1.0 - pairs / float((tiles * tiles).sum() * wl.batch), "route": route,
+                   "lists": args.lists},
         "attn_ms_per_call": attn_ms, "attn_ms_median": attn_ms_median,
         "attn_ms_min": attn_each[0], "attn_ms_max": attn_each[-1],
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
