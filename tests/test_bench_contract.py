@@ -43,6 +43,8 @@ def test_one_json_line_with_the_agreed_fields():
     roof = out["roofline"]
     assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s")
     assert roof["peak"] > 0 and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9
-    assert "traffic" in roof
+    assert "traffic" in roof and roof["traffic_source"]   # a tracked counter record, or the reason there is none
+    assert set(out["config"]["route"]) >= {"stage1", "stages23", "q", "k"}
+    assert "sclk_mhz" in out["diagnostics"]
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"] and cpu["unit"]
