@@ -35,7 +35,7 @@ PEAK_HBM_GBPS = 8000.0
 # copy kernel of known size.  A record is used only if it names the workload, tile size, keep
 # fraction and Q/K route of this run AND the hash of the attention kernel's sources as they are now;
 # otherwise traffic is null and traffic_source says why.
-KERNEL_SOURCES = ("attn_pair.hip", "attn_common.h", "attn.hip", "veda_internal.h", "geometry.h")
+KERNEL_SOURCES = ("attn_pair.hip", "attn_step.h", "attn_union.h", "attn_common.h", "attn.hip", "veda_internal.h", "geometry.h")
 
 
 def kernel_source_sha() -> str:
@@ -100,6 +100,9 @@ def parse():
     ap.add_argument("--exact-logit-scale", action="store_true",
                     help="VEDA_OPT_EXACT_LOGIT_SCALE: Q scaled by a power of two only, the rest of softmax_scale*log2(e) "
                          "applied to the logits in fp32 (error independent of the logits' size, about 4 % more time)")
+    ap.add_argument("--list-walk", action="store_true",
+                    help="VEDA_OPT_ATTN_LIST_WALK: the bf16 attention kernel merges the kept lists inside its loop "
+                         "instead of building its step table first")
     ap.add_argument("--lists", default="selected", choices=("selected", "partner", "head", "first"),
                     help="diagnostic for --attn-only (the outputs are no longer the method's): the kept lists the attention "
                          "call walks.  selected: as stages 2+3 chose them; partner: both query tiles of a workgroup get the "
@@ -259,6 +262,8 @@ def main():
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype, tile_tokens=B)
     if args.exact_logit_scale:
         plan.set_option(veda.VEDA_OPT_EXACT_LOGIT_SCALE, 1)
+    if args.list_walk:
+        plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 1)
     kph = wlm.keep_budget(wl, keep, shapes)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
@@ -295,9 +300,10 @@ def main():
     route = {"stage1": "gather + reread for descriptors" if args.unfused else "descriptors during the gather",
              "stages23": "two calls, score matrix in HBM" if args.two_stage else "one call, no score matrix",
              "q": "token order" if q_from_tokens else "tiled copy", "k": "token order" if k_from_tokens else "tiled copy",
-             "logit_scale": "exact (power of two into Q)" if args.exact_logit_scale else "default (Q pre-scaled, rounded once)"}
+             "logit_scale": "exact (power of two into Q)" if args.exact_logit_scale else "default (Q pre-scaled, rounded once)",
+             "steps": "lists merged inside the loop" if args.list_walk else "step table in LDS"}
     route_qk = ("tokens" if q_from_tokens else "tiled") + "," + ("tokens" if k_from_tokens else "tiled") + (
-        ",exact" if args.exact_logit_scale else "")
+        ",exact" if args.exact_logit_scale else "") + (",walk" if args.list_walk else "")
     bufs = {}
 
     def step(events=None):

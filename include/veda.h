@@ -97,8 +97,15 @@ void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
 
 /* Options of a plan; they take effect for the stage calls made after the setter returns.
  * VEDA_OPT_EXACT_LOGIT_SCALE (0 = off, the default; 1 = on), bf16 stage 4 (Eq. 2): see
- * veda_sparse_attn_fwd. */
-typedef enum { VEDA_OPT_EXACT_LOGIT_SCALE = 0 } veda_option;
+ * veda_sparse_attn_fwd.
+ * VEDA_OPT_ATTN_LIST_WALK (0 = off, the default; 1 = on), bf16 stage 4 (Sec. 4.3): the kernel
+ * normally works out, before its main loop, the order in which a workgroup visits the key tiles
+ * its query tiles keep (ascending, whatever the order inside the lists) into a table in LDS;
+ * with this option it merges the lists as it goes instead, reading them entry by entry (then
+ * ascending rows share the most loads).  The table covers heads of up to 16384 tiles; larger
+ * heads take the walk on their own.  Both orders give the same O up to rounding, and the same
+ * bits when the rows are ascending. */
+typedef enum { VEDA_OPT_EXACT_LOGIT_SCALE = 0, VEDA_OPT_ATTN_LIST_WALK = 1 } veda_option;
 veda_status veda_plan_set_option(veda_plan*, veda_option option, int32_t value);
 
 int32_t veda_plan_tiles(const veda_plan*, int32_t head);      /* N_T[h]; -1 on bad args        */

@@ -57,7 +57,7 @@ static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const v
     hipStream_t s = (hipStream_t)stream;
     if (pl->prob.dtype == VEDA_BF16) {
         a.xcd_cum = ip->d_xcd_cum_pair;
-        return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, pl->exact_logit_scale, s);
+        return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, pl->exact_logit_scale, pl->attn_list_walk, s);
     }
     a.xcd_cum = pl->d_xcd_cum_pair;
     return launch_sparse_attn_f32(pl, a, s);

@@ -148,7 +148,9 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // Launches the query-tile-pair bf16 kernel (attn_pair.hip) on plan pl's geometry; a.xcd_cum must be
 // its pair table.  grouped: pl is the inner plan of 128-token tiles and the CSR counts whole tiles.
 // exact: the power-of-two / residual split of the logit scale (AttnArgs::scale_pow2, scale_resid).
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, hipStream_t s);
+// walk: merge the kept lists inside the loop instead of building the step table first.
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, bool walk,
+                                         hipStream_t s);
 
 // The fp32 kernel (attn_f32.hip): same work items (a.xcd_cum must be the plan's pair table), tiled Q, K, V only.
 veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, hipStream_t s);

@@ -18,219 +18,19 @@
 // product.  K rows are loaded permuted by rho (bits 2,3 swapped) so that the eight keys a
 // lane-half owns are contiguous in the channel-major V tile.  One step of one wave:
 //     S^T block 0 (8 MFMA; in their shadow the wave's share of the NEXT tiles' global->LDS loads
-//                  and the next step of the list walk)
+//                  and the fetch of the step after next)
 //     S^T block 1 (8 MFMA; in their shadow the row maximum of block 0 and, speculatively, the
 //                  first 8 exponentials)
 //     one comparison: need the reference move, has the tile padded slots?   (rarely: the slow path)
 //     4 x [ 4 MFMA of O^T += V^T P^T ; the next 8 exponentials in their shadow ]   (at raised wave priority)
 // K/V tiles are double buffered (2 x 32 KB at d = 128) and filled by direct global->LDS loads
-// issued one step ahead.
-#include "attn_common.h"
+// issued one step ahead.  Which key tile comes at which step is worked out before the loop, by all
+// threads together, into a table in LDS (attn_union.h): a scalar-memory round trip inside the loop
+// would make every wait for an LDS operand a wait for everything.
+#include "attn_step.h"
+#include "attn_union.h"
 
 namespace veda {
-
-typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
-__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) { return *(lds_bf16x8_ptr)(uintptr_t)addr; }
-
-// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
-constexpr float kPairSlack = 8.0f;   // log2 units a row maximum may outgrow the softmax reference
-
-// Online-softmax state of one wave: 32 queries of one query tile (one per lane, duplicated in
-// the two lane halves).  qf holds Q scaled by softmax_scale*log2(e) (rounded to bf16 once), so
-// K Q^T is the logit in log2 units.  ref is the reference point of the exponentials in those
-// units: every S^T accumulator STARTS at -ref, so the MFMA chain delivers logit - ref and P is
-// a bare exp2 of it.  ref is moved (and S, O, l rescaled) on the first step and afterwards only
-// when some row maximum outgrows it by more than kPairSlack; any reference gives the same O
-// after the final division by l.
-template <int D> struct PairState {
-    f32x16 o[D / 32];
-    f32x16 start;        // -ref in every register: the C operand of the first MFMA of an S^T block
-    bf16x8 qf[D / 16];
-    float ref, l_run;
-    float resid;         // logits are held divided by this factor (see AttnArgs::scale_resid)
-    bool started;
-};
-
-// LDS addresses of the wave's operand fragments inside a slot.  The XOR swizzle only touches
-// address bits 4-7 (K) / 4-6 (V^T), which the row offsets leave clear, so one base per operand
-// is enough: K fragment (key block c, channel step t) is at (k0 ^ (t << 5)) + c * 32 rows,
-// V^T fragment (channel block nb, key step kk of 16 slots) at (v0 ^ (kk << 5)) + nb * 4096.
-struct PairAddr {
-    uint32_t k0, v0;
-    int hh;
-};
-
-// One key tile for one wave; slot = LDS byte offset of the (K tile, V^T tile) pair.
-// Issue order is pinned segment by segment (one MFMA each, scheduling barriers between): an
-// MFMA holds the matrix pipe for 32 cycles, a plain VALU op issues in 4 and exp2 in 8, so the
-// vector work placed in a segment runs in the MFMA's shadow.  LDS operand reads are issued
-// kAhead MFMAs before their consumer.
-//
-// What a wave has to do besides its MFMAs is spread over their shadows, so that the stretches
-// in which it offers the matrix pipe nothing are short (the SIMD's other wave, from the second
-// resident workgroup, only fills them when it happens to be in a product of its own):
-//   - the step comes in pieces (begin, block0<0..kSideCalls-1>, finish) between which the caller
-//     places its per-step housekeeping (the next tiles' global->LDS loads, the next step of the
-//     list walk): common code of all waves, not a second copy for the waves that skip the step,
-//     which for the active ones runs in the shadow of block 0's MFMAs;
-//   - the row maximum of block 0 and the exponentials of its first 8 registers ride on block 1's
-//     MFMAs.  The exponentials are speculative: they assume that the reference need not move and
-//     that the tile has no padded slot.  After block 1 one comparison per lane (no exchange
-//     between the lane halves: the test is "any lane of the wave") decides; in the rare other
-//     case the step falls back to masking, the exact row maximum, moving the reference and
-//     forming those exponentials again.
-constexpr int kSideCalls = 4;
-
-template <int D, bool kExact> struct PairStep {
-    static constexpr int G = D / 16, NB = D / 32, kAhead = 6;
-    static constexpr int kRowB = D * 2;
-    static constexpr int NF = 2 * G + 4 * NB;      // fragments per step: 2G of K, 4*NB of V^T
-    static_assert(G % kSideCalls == 0, "block 0's MFMAs are dealt evenly to the side calls");
-    static constexpr int kSeg = G / kSideCalls;    // MFMAs of block 0 before each side call
-    bf16x8 fr[NF];
-    bf16x8 pf[4];     // P^T operand of key step kk = 2c + s2: registers 8*s2..8*s2+7 of block c
-    f32x16 s[2];
-    uint32_t ka, va;
-    // Fragment f in issue order.  f < 2G: K fragment (c = f/G, t = f%G); then V^T fragments
-    // (kk = (f-2G)/NB, nb = (f-2G)%NB).
-#define VEDA_KF(f) lds_read16((ka ^ (uint32_t)(((f) % G) << 5)) + (uint32_t)(((f) / G) * 32 * kRowB))
-#define VEDA_VF(f) lds_read16((va ^ (uint32_t)(((f) / NB) << 5)) + (uint32_t)(((f) % NB) * 4096))
-#define VEDA_FRAG(f) ((f) < 2 * G ? VEDA_KF((f) < 2 * G ? (f) : 0) : VEDA_VF((f) < 2 * G ? 0 : (f) - 2 * G))
-
-    // The first operand reads of the step.
-    __device__ __forceinline__ void begin(const PairAddr& fa, uint32_t slot) {
-        ka = fa.k0 + slot;
-        va = fa.v0 + slot;
-#pragma unroll
-        for (int f = 0; f < kAhead; ++f) fr[f] = VEDA_FRAG(f);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // MFMAs kSeg*H .. kSeg*H + kSeg - 1 of S^T block 0; side call H follows them in the caller.
-    template <int H> __device__ __forceinline__ void block0(const PairState<D>& st) {
-#pragma unroll
-        for (int f = kSeg * H; f < kSeg * (H + 1); ++f) {
-            fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f], f == 0 ? st.start : s[0], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-
-    // S^T block 1, the softmax and O^T += V^T P^T.
-    __device__ __forceinline__ void finish(PairState<D>& st, const PairAddr& fa, uint64_t vm) {
-        float psum = 0.0f;
-        // P^T of key step kk: exponentials of registers 8*(kk%2)..+7 of block kk/2
-        // two scores at a time, so that the pair is rounded to bf16 by one packed conversion
-        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-#define VEDA_EXP(kk, e)                                                                         \
-    do {                                                                                        \
-        const float x0_ = s[(kk) >> 1][8 * ((kk) & 1) + (e)], x1_ = s[(kk) >> 1][8 * ((kk) & 1) + (e) + 1]; \
-        const float p0_ = __builtin_amdgcn_exp2f(kExact ? x0_ * st.resid : x0_);                \
-        const float p1_ = __builtin_amdgcn_exp2f(kExact ? x1_ * st.resid : x1_);                \
-        const bf16x2 pr_ = {(__bf16)p0_, (__bf16)p1_};                                          \
-        psum += p0_;                                                                            \
-        psum += p1_;                                                                            \
-        pf[kk][e] = pr_[0];                                                                     \
-        pf[kk][(e) + 1] = pr_[1];                                                               \
-    } while (0)
-        // S^T block 1.  Block 0's last MFMA needs two more to retire; then its row maximum (kMaxSeg
-        // MFMAs) and the speculative exponentials of its first 8 registers (the rest) ride along.
-        constexpr int kMaxSeg = G >= 8 ? 2 : 1, kExpSeg = G - 2 - kMaxSeg;
-        static_assert(kExpSeg >= 1 && 8 % kExpSeg == 0 && (8 / kExpSeg) % 2 == 0, "exponentials come in pairs");
-        float mx = -INFINITY;
-#pragma unroll
-        for (int f = G; f < 2 * G; ++f) {
-            fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], st.qf[f - G], f == G ? st.start : s[1], 0, 0, 0);
-            const int i = f - G - 2;
-            if (i >= 0 && i < kMaxSeg) {
-#pragma unroll
-                for (int e = i * (16 / kMaxSeg); e < (i + 1) * (16 / kMaxSeg); ++e) mx = fmaxf(mx, s[0][e]);
-            }
-            if (i >= kMaxSeg) {
-#pragma unroll
-                for (int e = (i - kMaxSeg) * (8 / kExpSeg); e < (i - kMaxSeg + 1) * (8 / kExpSeg); e += 2) VEDA_EXP(0, e);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-        // this lane's half of the row maximum is enough to see whether ANY row of the wave outgrew its reference
-        if (__builtin_expect(vm != ~0ull || !st.started || __any((kExact ? mx * st.resid : mx) > kPairSlack), 0)) {
-            // The empty asm keeps this a real branch: if-converted into the main block its ~150 vector
-            // ops would run on every step.
-            asm volatile("" ::: "memory");
-            if (vm != ~0ull) {
-                // Edge tile: padded key slots get -inf.  Register i of key block c is key slot
-                // 32c + 16*(i/8) + 8*hh + (i%8); the lane-dependent part is shifted out first so the
-                // per-register tests use constant bit positions.
-                mx = -INFINITY;
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const uint32_t half = (uint32_t)(vm >> (32 * c)) >> (8 * fa.hh);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        if (!((half >> (16 * (i >> 3) + (i & 7))) & 1u)) s[c][i] = -INFINITY;
-                        mx = fmaxf(mx, s[c][i]);
-                    }
-                }
-            }
-            mx = max_with_other_half(mx);   // row maximum relative to the reference
-            if (!st.started || __any((kExact ? mx * st.resid : mx) > kPairSlack)) {
-                // Move the reference of every row whose maximum is above it (first step: to the
-                // maximum itself, up or down).
-                float delta = st.started ? fmaxf(mx, 0.0f) : mx;
-                delta = delta == -INFINITY ? 0.0f : delta;
-                const float alpha = st.started ? __builtin_amdgcn_exp2f(kExact ? -delta * st.resid : -delta) : 1.0f;   // O = l = 0 before
-                st.ref += delta;
-                st.l_run *= alpha;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) st.start[i] = -st.ref;
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s[c][i] -= delta;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) st.o[nb][i] *= alpha;
-                st.started = true;
-            }
-            psum = 0.0f;   // the speculative exponentials are void
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) VEDA_EXP(0, e);
-        }
-        // The wave that has reached its O^T products goes first at the issue port: the other wave
-        // of the SIMD (in its own softmax section, all vector ops) otherwise delays these MFMAs and
-        // the matrix pipe idles.  Measured: 6 % fewer cycles for the whole kernel.
-        __builtin_amdgcn_s_setprio(1);
-        __builtin_amdgcn_sched_barrier(0);
-        // O^T += V^T P^T; the 8 exponentials of the next key step are spread over this key step's
-        // NB MFMAs
-#pragma unroll
-        for (int g = 0; g < 4 * NB; ++g) {
-            const int f = 2 * G + g;
-            if (f + kAhead < NF) fr[f + kAhead] = VEDA_FRAG(f + kAhead);
-            const int kk = g / NB, nb = g % NB;
-            st.o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f], pf[kk], st.o[nb], 0, 0, 0);
-            if (kk < 3) {
-#pragma unroll
-                for (int e = nb * (8 / NB); e < (nb + 1) * (8 / NB); e += 2) VEDA_EXP(kk + 1, e);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_s_setprio(0);
-        st.l_run += psum;
-#undef VEDA_EXP
-    }
-#undef VEDA_FRAG
-#undef VEDA_KF
-#undef VEDA_VF
-};
 
 // After the last step: normalise, transpose through LDS and scatter the real rows of the
 // workgroup's two query tiles to token order.  obuf: [2 tiles][64 rows][D] bf16, then lse_s and tok_s.
@@ -292,7 +92,11 @@ struct MergedStep {
 // kTokK: K is read from token order (a.k_tok) instead of the tiled tensor: a key tile's rows
 // are found at first-token + (lt*H + lh)*W + lw; the rows of padded slots are fetched from slot 0
 // instead (any finite or non-finite value will do: their logits are overwritten with -inf).
-template <int D, bool kGrouped, bool kTokK, bool kExact>
+// kTable: the steps come from a table in LDS built before the main loop (attn_union.h; heads of up
+// to 16384 whole tiles); otherwise the lists are walked with scalar loads as the loop goes.
+constexpr int kPairChunk = 128;   // step-table entries filled at a time
+
+template <int D, bool kGrouped, bool kTokK, bool kExact, bool kTable>
 __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs a) {
     constexpr int kRowB = D * 2;                 // bytes of one K row
     constexpr int kKBytes = kTile * kRowB;       // K tile
@@ -422,23 +226,51 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     fa.k0 = smem_base + rho(lq) * kRowB + ((hh ^ (lq & (kKChunks - 1))) << 4);
     fa.v0 = smem_base + kKBytes + lq * 128 + ((hh ^ (((lq >> 1) & 7) ^ ((lq & 1) << 2))) << 4);
 
-    // Merged walk: at every step take the smaller of the two list heads; a key tile kept by
-    // both query tiles is loaded once and used by both halves of the workgroup.  (Ascending
-    // lists, as stage 3 writes them, share the most; any order stays correct.)
-    // The list heads are kept as (raw loaded value, in-range flag) and only combined when the
-    // next step is formed, one step later: the scalar loads get a whole step to return.
-    // A step is formed in two halves (next_head: which tile and who keeps it; next_advance: move
-    // the list positions and fetch the new heads) so that each fits the shadow of one MFMA.
-    // Everything of the walk is kept in 32-bit integers (flags as 0/1, never as booleans) and the
-    // step's flags pass through readfirstlane: the walk then stays on the scalar unit and the
-    // branches on it are scalar branches.
+    // The steps: every key tile kept by at least one of the two query tiles, once; a key tile kept by
+    // both is loaded once and used by both halves of the workgroup.
+    // Table mode: the sequence is laid out in LDS before the loop (attn_union.h: ascending union,
+    // whatever the order inside the lists) and the loop reads one entry per step, ahead of its use.
+    // Walk mode: at every step take the smaller of the two list heads (ascending lists, as stage 3
+    // writes them, share the most; any order stays correct).  The list heads are kept as (raw loaded
+    // value, in-range flag) and only combined when the next step is formed, one step later: the scalar
+    // loads get a whole step to return.  A step is formed in two halves (next_head: which tile and who
+    // keeps it; next_advance: move the list positions and fetch the new heads) so that each fits the
+    // shadow of one MFMA.  Everything of the walk is kept in 32-bit integers (flags as 0/1, never as
+    // booleans) and the step's flags pass through readfirstlane: the walk then stays on the scalar
+    // unit and the branches on it are scalar branches.
     constexpr int kEnd = 0x7fffffff;
     int ia = 0, ib = 0;
-    int rawA = colsA[0], rawB = colsB[0];
-    int okA = nA > 0 ? 1 : 0, okB = nB > 0 ? 1 : 0;
+    int rawA = 0, rawB = 0, okA = 0, okB = 0;
     int gh = 0;         // grouped walk: which half of the current entry comes next
     int ta = 0, tb = 0; // this step consumes the head of list A / B
+    // table mode: the raw entry read one step ahead of its use, the next entry to read, steps done
+    typedef UnionLds<2, kPairChunk> Table;
+    Table& u = *reinterpret_cast<Table*>(smem + 2 * kSlot);
+    const uint32_t tab_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)&u.tab[0];
+    i32x4 raw_next = {0, 0, 0, 0};
+    int s_read = 0, s_done = 0, total = 0;
+    const int list_range = kGrouped ? hg.n_tiles / 2 : hg.n_tiles;
+    const uint64_t* vmask_g = a.valid_mask + hg.tile_off;
+    const int32_t* n0s_g = a.tile_n0 + hg.tile_off;
+    if constexpr (kTable) {
+        const int32_t* lists[2] = {a.col_idx + begA, a.col_idx + begB};
+        const int counts[2] = {nA, kGrouped ? 0 : nB};
+        total = union_build<2, 256, kPairChunk>(u, lists, counts, list_range, tid) * (kGrouped ? 2 : 1);
+        union_fill<2, 256, kPairChunk, kGrouped>(u, 0, total, list_range, vmask_g, n0s_g, tid);
+        union_fill<2, 256, kPairChunk, kGrouped>(u, kPairChunk, total, list_range, vmask_g, n0s_g, tid);
+        __syncthreads();
+    } else {
+        rawA = colsA[0];
+        rawB = colsB[0];
+        okA = nA > 0 ? 1 : 0;
+        okB = nB > 0 ? 1 : 0;
+    }
     auto next_head = [&](MergedStep& e) __attribute__((always_inline)) {
+        if constexpr (kTable) {
+            const UnionStep t = union_step(raw_next);
+            e.j = t.j; e.fl = t.fl; e.vm = t.vm; e.n0 = t.n0;
+            return;
+        }
         int j, fl;
         if (kGrouped) {
             j = okA ? 2 * rawA + gh : 0;
@@ -459,6 +291,11 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
         e.n0 = kTokK ? n0s[e.j] : 0;
     };
     auto next_advance = [&]() __attribute__((always_inline)) {
+        if constexpr (kTable) {
+            raw_next = union_read<kPairChunk>(tab_lds, s_read);
+            ++s_read;
+            return;
+        }
         ia += ta;
         okA = ia < nA ? 1 : 0;
         rawA = colsA[okA ? ia : 0];
@@ -470,6 +307,16 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
             rawB = colsB[okB ? ib : 0];
         }
     };
+    // After the barrier that ends a step (table mode): when the loop has left one half of the
+    // table's ring, that half is refilled with the steps that follow the other half's.
+    auto step_done = [&]() __attribute__((always_inline)) {
+        if constexpr (kTable) {
+            ++s_done;
+            if ((s_done & (kPairChunk - 1)) == 0)
+                union_fill<2, 256, kPairChunk, kGrouped>(u, s_done + kPairChunk, total, list_range, vmask_g, n0s_g, tid);
+        }
+    };
+    if constexpr (kTable) next_advance();   // entry 0 on its way
 
     // Step s (P = s & 1) computes on slot P while the tiles of step s+1 land in slot P^1.
     const int my_bit = 1 << which;
@@ -492,7 +339,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     do {                                                                                                 \
         int todo = 1;                                                                                    \
         if (__builtin_expect((e0.fl & my_bit) != 0, 1)) {                                                \
-            PairStep<D, kExact> w;                                                                            \
+            PairStep<D, kExact> w;                                                                       \
             w.begin(fa, (uint32_t)((P) * kSlot));                                                        \
             w.template block0<0>(st);                                                                    \
             if (e1.fl) load_tile(e1, (P) ^ 1, 0);                                                        \
@@ -516,6 +363,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
         }                                                                                                \
         e0 = e1; e1 = e2;                                                                                \
         VEDA_LOADS_DONE_BARRIER();                                                                       \
+        step_done();                                                                                     \
     } while (0)
     while (e0.fl) {
         VEDA_STEP(0);
@@ -528,14 +376,28 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_pair_kernel(AttnArgs 
     finish_pair<D>(st, a, hg, smem, head, qiA, qiB, hasB, b, tid, which, r, lq, hh);
 }
 
-veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, hipStream_t s) {
+veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a, bool grouped, bool exact, bool walk,
+                                         hipStream_t s) {
     const int d = pl->prob.head_dim;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
-    const size_t smem = (size_t)2 * 2 * kTile * d * 2;   // two slots of (K tile + V^T tile)
+    // the step table needs a bitmap over the tiles the lists may name
+    bool table = !walk;
+    for (const HeadGeom& g : pl->heads) table = table && (grouped ? g.n_tiles / 2 : g.n_tiles) <= kUnionMaxTiles;
+    // two slots of (K tile + V^T tile), then the step table
+    const size_t smem = (size_t)2 * 2 * kTile * d * 2 + (table ? sizeof(UnionLds<2, kPairChunk>) : 0);
+#define VEDA_LAUNCH_PAIR_T(DD, GG, KK, EE, TT)                                                           \
+    do {                                                                                                 \
+        auto kern = sparse_attn_bf16_pair_kernel<DD, GG, KK, EE, TT>;                                    \
+        if (smem > 64 * 1024)                                                                            \
+            VEDA_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)); \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, a);                                               \
+    } while (0)
 #define VEDA_LAUNCH_PAIR(DD, GG, KK)                                                                     \
     do {                                                                                                 \
-        if (exact) hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK, true>), grid, block, smem, s, a);   \
-        else hipLaunchKernelGGL((sparse_attn_bf16_pair_kernel<DD, GG, KK, false>), grid, block, smem, s, a);        \
+        if (exact && table) VEDA_LAUNCH_PAIR_T(DD, GG, KK, true, true);                                  \
+        else if (exact) VEDA_LAUNCH_PAIR_T(DD, GG, KK, true, false);                                     \
+        else if (table) VEDA_LAUNCH_PAIR_T(DD, GG, KK, false, true);                                     \
+        else VEDA_LAUNCH_PAIR_T(DD, GG, KK, false, false);                                               \
     } while (0)
     const int variant = (d == 128 ? 4 : 0) | (grouped ? 2 : 0) | (a.k_tok ? 1 : 0);
     switch (variant) {
@@ -549,6 +411,7 @@ veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a,
         default: VEDA_LAUNCH_PAIR(128, true, true); break;
     }
 #undef VEDA_LAUNCH_PAIR
+#undef VEDA_LAUNCH_PAIR_T
     return launch_status("sparse_attn_bf16_pair_kernel");
 }
 

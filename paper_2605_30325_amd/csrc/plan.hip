@@ -216,6 +216,10 @@ veda_status veda_plan_set_option(veda_plan* pl, veda_option option, int32_t valu
             if (value != 0 && value != 1) return VEDA_ERR_INVALID_ARG;
             pl->exact_logit_scale = value != 0;
             return VEDA_OK;
+        case VEDA_OPT_ATTN_LIST_WALK:
+            if (value != 0 && value != 1) return VEDA_ERR_INVALID_ARG;
+            pl->attn_list_walk = value != 0;
+            return VEDA_OK;
     }
     return VEDA_ERR_INVALID_ARG;
 }

@@ -62,6 +62,7 @@ struct veda_plan {
     int64_t score_blocks = 0;
     int device = -1;
     bool exact_logit_scale = false;     // VEDA_OPT_EXACT_LOGIT_SCALE (bf16 attention kernel)
+    bool attn_list_walk = false;        // VEDA_OPT_ATTN_LIST_WALK (bf16 attention kernel)
     // 128-token tiles: this plan describes the whole tiles (stages 2 and 3 work on them); `inner`
     // describes their 64-slot halves, in the order 2o, 2o+1 (stages 1 and 4 work on those).
     veda_plan* inner = nullptr;

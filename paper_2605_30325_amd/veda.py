@@ -22,6 +22,7 @@ VEDA_F32, VEDA_BF16 = 0, 1
 VEDA_ACT_IDENTITY, VEDA_ACT_RELU = 0, 1
 VEDA_TOKEN_MAJOR, VEDA_CHANNEL_MAJOR = 0, 1
 VEDA_OPT_EXACT_LOGIT_SCALE = 0
+VEDA_OPT_ATTN_LIST_WALK = 1
 
 EXPORTS = (
     "veda_plan_create", "veda_plan_destroy", "veda_plan_set_option", "veda_plan_tiles", "veda_plan_tile_offset",

@@ -195,12 +195,14 @@ def test_row_stochastic_weights_on_gpu():
     assert (out.float() - 1.0).abs().max().item() <= 2 ** -7
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64)])
-def test_attention_on_hand_made_lists(dtype, d):
+@pytest.mark.parametrize("dtype,d,walk", [("bf16", 128, False), ("bf16", 64, False), ("f32", 64, False),
+                                          ("bf16", 128, True), ("bf16", 64, True)])
+def test_attention_on_hand_made_lists(dtype, d, walk):
     # Stage 4 alone on kept lists that stage 3 would never write: unsorted, neighbours with
     # identical / disjoint / partly shared lists.  The grid gives every head an odd tile count
-    # (the last query tile has no neighbour) and ragged tiles on every axis.
-    _hand_made_lists(dtype, d, 1.0, 1.0)
+    # (the last query tile has no neighbour) and ragged tiles on every axis.  walk: the bf16 kernel
+    # merging the lists inside its loop (VEDA_OPT_ATTN_LIST_WALK) instead of from its step table.
+    _hand_made_lists(dtype, d, 1.0, 1.0, walk=walk)
 
 
 def test_attention_with_large_logits_fp32():
@@ -229,7 +231,7 @@ def test_bf16_attention_error_against_logit_size():
     st = _hand_made_lists("bf16", 64, 6.0, 1.0, check=True, exact_scale=True)   # d = 64: residual factor 1.44
 
 
-def _hand_made_lists(dtype, d, q_gain, tol_gain, check=True, exact_scale=False):
+def _hand_made_lists(dtype, d, q_gain, tol_gain, check=True, exact_scale=False, walk=False):
     wl = wlm.custom_workload(f"lists_{dtype}_{d}", 3, d, dtype, (9, 18, 18), True, (25, 100), seed=31)
     dev = torch.device("cuda:0")
     shapes = wlm.tile_shapes(wl)
@@ -238,6 +240,8 @@ def _hand_made_lists(dtype, d, q_gain, tol_gain, check=True, exact_scale=False):
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
     if exact_scale:
         plan.set_option(veda.VEDA_OPT_EXACT_LOGIT_SCALE, 1)
+    if walk:
+        plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 1)
     assert all(n % 2 for n in plan.tiles)
     qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
     kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
@@ -635,6 +639,16 @@ def test_attention_with_q_in_token_order(d, tile_tokens):
     torch.cuda.synchronize()
     assert torch.equal(out1.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse1, lse2)
     assert torch.equal(out1.view(torch.int16), out3.view(torch.int16)) and torch.equal(lse1, lse3)
+    # ascending rows: the lists merged inside the loop visit the key tiles in the step table's order
+    plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 1)
+    out4, lse4 = veda.veda_sparse_attn_fwd(plan, qt, kt, vt, vm, row_ptr, col_idx, scale, want_lse=True)
+    out5 = torch.full_like(out1, float("nan"))
+    out5, lse5 = veda.veda_sparse_attn_fwd(plan, None, None, vt, vm, row_ptr, col_idx, scale, out=out5, want_lse=True,
+                                           q_tokens=qpad[..., :d], k_tokens=kpad[..., :d])
+    plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(out1.view(torch.int16), out4.view(torch.int16)) and torch.equal(lse1, lse4)
+    assert torch.equal(out1.view(torch.int16), out5.view(torch.int16)) and torch.equal(lse1, lse5)
     if tile_tokens == 64:
         _, vm_a, vc_a, z_a = veda.veda_tile_layout_stats(plan, q)
         none, vm_b, vc_b, z_b = veda.veda_tile_layout_stats(plan, q, want_tiles=False)
