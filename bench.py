@@ -100,6 +100,9 @@ def parse():
     ap.add_argument("--exact-logit-scale", action="store_true",
                     help="VEDA_OPT_EXACT_LOGIT_SCALE: Q scaled by a power of two only, the rest of softmax_scale*log2(e) "
                          "applied to the logits in fp32 (error independent of the logits' size, about 4 % more time)")
+    ap.add_argument("--fp32-chains", default="probed", choices=("probed", "matrix", "vector"),
+                    help="VEDA_OPT_FP32_CHAIN_UNIT: where the projections' (and a score matrix's) fp32 chains run; "
+                         "probed = what the library's probe of this device allows (the matrix cores on gfx950)")
     ap.add_argument("--list-walk", action="store_true",
                     help="VEDA_OPT_ATTN_LIST_WALK: the bf16 attention kernel merges the kept lists inside its loop "
                          "instead of building its step table first")
@@ -264,6 +267,9 @@ def main():
         plan.set_option(veda.VEDA_OPT_EXACT_LOGIT_SCALE, 1)
     if args.list_walk:
         plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 1)
+    if args.fp32_chains != "probed":
+        plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT,
+                        veda.VEDA_CHAINS_MATRIX if args.fp32_chains == "matrix" else veda.VEDA_CHAINS_VECTOR)
     kph = wlm.keep_budget(wl, keep, shapes)
     eq, ek = wlm.make_estimator(wl, "q"), wlm.make_estimator(wl, "k")
     pq = veda.Mlp(eq.w1, eq.b1, eq.w2, eq.b2, eq.relu, dev)
@@ -301,7 +307,8 @@ def main():
              "stages23": "two calls, score matrix in HBM" if args.two_stage else "one call, no score matrix",
              "q": "token order" if q_from_tokens else "tiled copy", "k": "token order" if k_from_tokens else "tiled copy",
              "logit_scale": "exact (power of two into Q)" if args.exact_logit_scale else "default (Q pre-scaled, rounded once)",
-             "steps": "lists merged inside the loop" if args.list_walk else "step table in LDS"}
+             "steps": "lists merged inside the loop" if args.list_walk else "step table in LDS",
+             "fp32_chains": "matrix cores" if plan.chain_unit() == veda.VEDA_CHAINS_MATRIX else "vector units"}
     route_qk = ("tokens" if q_from_tokens else "tiled") + "," + ("tokens" if k_from_tokens else "tiled") + (
         ",exact" if args.exact_logit_scale else "") + (",walk" if args.list_walk else "")
     bufs = {}

@@ -104,9 +104,19 @@ void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
  * with this option it merges the lists as it goes instead, reading them entry by entry (then
  * ascending rows share the most loads).  The table covers heads of up to 16384 tiles; larger
  * heads take the walk on their own.  Both orders give the same O up to rounding, and the same
- * bits when the rows are ascending. */
-typedef enum { VEDA_OPT_EXACT_LOGIT_SCALE = 0, VEDA_OPT_ATTN_LIST_WALK = 1 } veda_option;
+ * bits when the rows are ascending.
+ * VEDA_OPT_FP32_CHAIN_UNIT (0 = as probed, the default; VEDA_CHAINS_MATRIX; VEDA_CHAINS_VECTOR),
+ * stage 2 (Eq. 5): where the fixed-order fp32 chains of the projections and of the score matrix
+ * run.  They are defined as scalar fmaf chains; on gfx950 chains of v_mfma_f32_32x32x2_f32 give
+ * the same bits at twice the rate, which is a measured property of that instruction.
+ * veda_plan_create measures it on the plan's device (both forms on chains with rounding,
+ * signed zeros and denormal sums and products, once per device) and uses the matrix cores only
+ * if every bit agrees; this option overrides the choice either way.
+ * veda_plan_chain_unit tells which unit the plan's next call will use. */
+typedef enum { VEDA_OPT_EXACT_LOGIT_SCALE = 0, VEDA_OPT_ATTN_LIST_WALK = 1, VEDA_OPT_FP32_CHAIN_UNIT = 2 } veda_option;
+enum { VEDA_CHAINS_MATRIX = 1, VEDA_CHAINS_VECTOR = 2 };
 veda_status veda_plan_set_option(veda_plan*, veda_option option, int32_t value);
+int32_t veda_plan_chain_unit(const veda_plan*);          /* VEDA_CHAINS_*; -1 on bad args */
 
 int32_t veda_plan_tiles(const veda_plan*, int32_t head);      /* N_T[h]; -1 on bad args        */
 int64_t veda_plan_tile_offset(const veda_plan*, int32_t head);/* tile_off[h] = sum_{h'<h} N_T  */
@@ -145,9 +155,11 @@ veda_status veda_tile_layout(const veda_plan*, const void* x, veda_strides sx, v
  * implementation of that order gives the same bits.  On gfx950 the projection chains and the
  * chains of veda_tile_score's score matrix are issued as v_mfma_f32_32x32x2_f32 over ascending
  * index pairs: that this instruction applies its two terms one after the other, each rounded as
- * an fma, denormals kept, is a property measured on gfx950 (and pinned by the parity tests), not
- * one its ISA manual states; the fused route (veda_tile_score_select*) forms its scores with
- * plain fmaf chains on the vector units.
+ * an fma, denormals kept, is a property measured on gfx950, not one its ISA manual states: the
+ * library measures it again on every device it meets (veda_plan_create) and runs these chains as
+ * scalar fmaf on the vector units wherever a bit differs (VEDA_OPT_FP32_CHAIN_UNIT forces either
+ * form).  The fused route (veda_tile_score_select*) forms its scores with plain fmaf chains on
+ * the vector units in any case; its projections follow the same choice.
  * workspace device scratch of at least veda_plan_workspace_bytes().  After the call it holds the
  * stage's intermediates at the float offsets veda_plan_workspace_layout() reports (descriptors
  * and latents, one row per (batch, global tile)); the rest is undefined. */

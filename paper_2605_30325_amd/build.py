@@ -18,10 +18,10 @@ CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libveda.so"
 
-SOURCES = ["plan.hip", "layout.hip", "score.hip", "select.hip", "fused.hip", "attn.hip", "attn_pair.hip", "attn_f32.hip", "heatmap.hip"]
+SOURCES = ["plan.hip", "layout.hip", "score.hip", "chains_vector.hip", "select.hip", "fused.hip", "attn.hip", "attn_pair.hip", "attn_f32.hip", "heatmap.hip"]
 COMMON = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", f"-I{ROOT / 'include'}", f"-I{CSRC}",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
-PER_FILE = {"score.hip": ["-ffp-contract=off"], "fused.hip": ["-ffp-contract=off"]}
+PER_FILE = {"score.hip": ["-ffp-contract=off"], "fused.hip": ["-ffp-contract=off"], "chains_vector.hip": ["-ffp-contract=off"]}
 
 
 def hipcc() -> str:

@@ -135,7 +135,9 @@ static veda_status build_plan(const veda_problem* p, const int32_t* shapes, int 
     if (e == hipSuccess) {
         // set-up call of this device: the no-allocation entry point finds its scratch array resolved
         void* unused = nullptr;
-        const veda_status ns = veda::noalloc_scratch(pl->device, &unused);
+        veda_status ns = veda::noalloc_scratch(pl->device, &unused);
+        // ... and knows which unit reproduces the fp32 chains of stage 2
+        if (ns == VEDA_OK) ns = veda::probe_chain_unit(pl->device, &pl->chain_probe);
         if (ns != VEDA_OK) {
             delete pl;
             return ns;
@@ -220,9 +222,16 @@ veda_status veda_plan_set_option(veda_plan* pl, veda_option option, int32_t valu
             if (value != 0 && value != 1) return VEDA_ERR_INVALID_ARG;
             pl->attn_list_walk = value != 0;
             return VEDA_OK;
+        case VEDA_OPT_FP32_CHAIN_UNIT:
+            if (value != 0 && value != VEDA_CHAINS_MATRIX && value != VEDA_CHAINS_VECTOR) return VEDA_ERR_INVALID_ARG;
+            pl->chain_option = value;
+            if (pl->inner) pl->inner->chain_option = value;
+            return VEDA_OK;
     }
     return VEDA_ERR_INVALID_ARG;
 }
+
+int32_t veda_plan_chain_unit(const veda_plan* pl) { return pl ? pl->chain_unit() : -1; }
 
 int32_t veda_plan_tiles(const veda_plan* pl, int32_t head) {
     if (!pl || head < 0 || head >= pl->prob.heads) return -1;

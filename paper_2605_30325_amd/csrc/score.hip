@@ -84,11 +84,6 @@ __global__ __launch_bounds__(256) void trippool_kernel(const char* __restrict__ 
     }
 }
 
-struct MlpDev {
-    int in_dim, hidden, out_dim, relu;
-    const float *w1, *b1, *w2, *b2;
-};
-
 constexpr int kMlpRows = 64;       // tiles per workgroup
 constexpr int kMlpCols = 128;      // output units per pass
 constexpr int kMlpK = 16;          // reduction indices staged per step
@@ -433,6 +428,7 @@ veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const
                                const float* zk, float* yq, float* yk, float* hq, float* hk, hipStream_t s) {
     MlpDev pq{phi_q->in_dim, phi_q->hidden, phi_q->out_dim, phi_q->act == VEDA_ACT_RELU, phi_q->w1, phi_q->b1, phi_q->w2, phi_q->b2};
     MlpDev pk{phi_k->in_dim, phi_k->hidden, phi_k->out_dim, phi_k->act == VEDA_ACT_RELU, phi_k->w1, phi_k->b1, phi_k->w2, phi_k->b2};
+    if (pl->chain_unit() == VEDA_CHAINS_VECTOR) return launch_projections_vector(pl, pq, pk, zq, zk, yq, yk, s);
     const int max_hidden = phi_q->hidden > phi_k->hidden ? phi_q->hidden : phi_k->hidden;
     // the global route reads the hidden layer back as float4 rows
     if (!hq || !hk || (phi_q->hidden & 3) || (phi_k->hidden & 3)) hq = hk = nullptr;
@@ -451,6 +447,7 @@ veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const
 // that touch a marked group are formed.
 veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
                                 float scale, const int32_t* marks, hipStream_t s) {
+    if (pl->chain_unit() == VEDA_CHAINS_VECTOR) return launch_score_blocks_vector(pl, yq, yk, scores, dp, scale, marks, s);
     if (marks) {
         dim3 rgrid((unsigned)pl->row_blocks, (unsigned)pl->prob.batch);
         hipLaunchKernelGGL(score_marked_rows_kernel, rgrid, dim3(256), 0, s, pl->d_heads, pl->d_row_blk, yq, yk, scores,

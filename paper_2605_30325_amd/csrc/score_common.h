@@ -8,6 +8,12 @@ namespace veda {
 
 constexpr int kLatentRows = 64;   // rows of one row block of the plan's d_row_blk table
 
+// One estimator as the kernels take it (device pointers, per-head arrays back to back).
+struct MlpDev {
+    int in_dim, hidden, out_dim, relu;
+    const float *w1, *b1, *w2, *b2;
+};
+
 // Argument check of one estimator (shapes against the plan, supported sizes).
 veda_status check_mlp(const veda_plan* pl, const veda_mlp* m);
 
@@ -26,5 +32,13 @@ veda_status launch_projections(const veda_plan* pl, const veda_mlp* phi_q, const
 // that touch a marked group are formed.
 veda_status launch_score_blocks(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
                                 float scale, const int32_t* marks, hipStream_t s);
+
+// The same two launches with every chain as scalar fmaf on the vector units (chains_vector.hip): the
+// form the arithmetic is defined by, kept selectable (VEDA_OPT_FP32_CHAIN_UNIT) and taken on its own
+// on a device where the matrix-core form does not reproduce it (probe_chain_unit).
+veda_status launch_projections_vector(const veda_plan* pl, const MlpDev& pq, const MlpDev& pk, const float* zq,
+                                      const float* zk, float* yq, float* yk, hipStream_t s);
+veda_status launch_score_blocks_vector(const veda_plan* pl, const float* yq, const float* yk, float* scores, int dp,
+                                       float scale, const int32_t* marks, hipStream_t s);
 
 }  // namespace veda

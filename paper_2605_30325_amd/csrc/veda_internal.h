@@ -63,6 +63,10 @@ struct veda_plan {
     int device = -1;
     bool exact_logit_scale = false;     // VEDA_OPT_EXACT_LOGIT_SCALE (bf16 attention kernel)
     bool attn_list_walk = false;        // VEDA_OPT_ATTN_LIST_WALK (bf16 attention kernel)
+    // Where the fixed-order fp32 chains of stage 2 run: chain_probe is what probe_chain_unit found on
+    // this plan's device, chain_option what VEDA_OPT_FP32_CHAIN_UNIT asks for (0 = as probed).
+    int chain_probe = VEDA_CHAINS_MATRIX, chain_option = 0;
+    int chain_unit() const { return chain_option ? chain_option : chain_probe; }
     // 128-token tiles: this plan describes the whole tiles (stages 2 and 3 work on them); `inner`
     // describes their 64-slot halves, in the order 2o, 2o+1 (stages 1 and 4 work on those).
     veda_plan* inner = nullptr;
@@ -89,6 +93,8 @@ namespace veda {
 
 void set_last_error(const std::string& s);
 veda_status hip_fail(hipError_t e, const char* what);
+// chains_vector.hip: VEDA_CHAINS_MATRIX or VEDA_CHAINS_VECTOR for the fp32 chains of stage 2 on GPU `device` (the current one).
+veda_status probe_chain_unit(int device, int* unit);
 
 #define VEDA_HIP_TRY(expr)                                              \
     do {                                                                \

@@ -23,9 +23,11 @@ VEDA_ACT_IDENTITY, VEDA_ACT_RELU = 0, 1
 VEDA_TOKEN_MAJOR, VEDA_CHANNEL_MAJOR = 0, 1
 VEDA_OPT_EXACT_LOGIT_SCALE = 0
 VEDA_OPT_ATTN_LIST_WALK = 1
+VEDA_OPT_FP32_CHAIN_UNIT = 2
+VEDA_CHAINS_MATRIX, VEDA_CHAINS_VECTOR = 1, 2
 
 EXPORTS = (
-    "veda_plan_create", "veda_plan_destroy", "veda_plan_set_option", "veda_plan_tiles", "veda_plan_tile_offset",
+    "veda_plan_create", "veda_plan_destroy", "veda_plan_set_option", "veda_plan_chain_unit", "veda_plan_tiles", "veda_plan_tile_offset",
     "veda_plan_score_offset", "veda_plan_total_tiles", "veda_plan_score_elems",
     "veda_plan_workspace_bytes", "veda_plan_workspace_layout", "veda_tile_layout", "veda_tile_score", "veda_tile_layout_stats",
     "veda_tile_score_stats", "veda_tile_score_closed_form", "veda_tile_select", "veda_plan_fused_workspace_bytes",
@@ -79,6 +81,8 @@ def load():
     L.veda_plan_destroy.restype = None
     L.veda_plan_set_option.argtypes = [vp, C.c_int, i32]
     L.veda_plan_set_option.restype = C.c_int
+    L.veda_plan_chain_unit.argtypes = [vp]
+    L.veda_plan_chain_unit.restype = i32
     L.veda_plan_tiles.argtypes = [vp, i32]
     L.veda_plan_tiles.restype = i32
     for name in ("veda_plan_tile_offset", "veda_plan_score_offset"):
@@ -212,6 +216,10 @@ class Plan:
 
     def set_option(self, option: int, value: int):
         _check(load().veda_plan_set_option(self.handle, option, int(value)), "veda_plan_set_option")
+
+    def chain_unit(self) -> int:
+        """VEDA_CHAINS_MATRIX or VEDA_CHAINS_VECTOR: where the plan's next stage-2 call runs its fp32 chains."""
+        return int(load().veda_plan_chain_unit(self.handle))
 
     def workspace_bytes(self, phi_q: Mlp, phi_k: Mlp) -> int:
         return int(load().veda_plan_workspace_bytes(self.handle, C.byref(phi_q.struct()), C.byref(phi_k.struct())))

@@ -60,10 +60,14 @@ def test_batch_two_and_strided_input():
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
-@pytest.mark.parametrize("hidden,dp,relu", [(0, 12, True), (20, 12, True), (131, 8, False), (260, 200, True)])
-def test_estimator_shapes_bit_exact(hidden, dp, relu):
+@pytest.mark.parametrize("hidden,dp,relu,unit", [(0, 12, True, 0), (20, 12, True, 0), (131, 8, False, 0),
+                                                  (260, 200, True, 0), (0, 12, True, 2), (131, 8, False, 2),
+                                                  (260, 200, True, 2)])
+def test_estimator_shapes_bit_exact(hidden, dp, relu, unit):
     # widths that are not multiples of the kernel's blocking, a single affine layer, no ReLU;
-    # 135..180 tiles per head: several 64-row blocks and 128x128 score blocks, all with ragged tails
+    # 135..180 tiles per head: several 64-row blocks and 128x128 score blocks, all with ragged tails.
+    # unit = 2: the chains as scalar fmaf on the vector units (VEDA_OPT_FP32_CHAIN_UNIT), the form that
+    # defines them; unit = 0: where the library's probe of this device put them (the matrix cores on gfx950)
     wl = wlm.custom_workload(f"mlp_{hidden}_{dp}", 2, 64, "f32", (10, 20, 36), True, (50, 100), seed=21,
                              latent_dim=dp)
     _say(f"[parity] {wl.name}: estimator 192 -> {hidden} -> {dp} relu={relu}")
@@ -83,6 +87,9 @@ def test_estimator_shapes_bit_exact(hidden, dp, relu):
     wq, wk = weights(), weights()
     q, k, _ = wlm.make_qkv(wl, dev)
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    if unit:
+        plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT, unit)
+        assert plan.chain_unit() == unit
     qt, vm, _ = veda.veda_tile_layout(plan, q, veda.VEDA_TOKEN_MAJOR)
     kt, _, _ = veda.veda_tile_layout(plan, k, veda.VEDA_TOKEN_MAJOR, want_mask=False)
     scale = hz.score_scale_of(wl)
@@ -99,6 +106,22 @@ def test_estimator_shapes_bit_exact(hidden, dp, relu):
         nt, soff = plan.tiles[h], plan.score_offset[h]
         got = s[0, soff:soff + nt * nt].view(nt, nt).cpu().numpy()
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"{wl.name} head {h}: scores not bit-exact"
+
+
+def test_this_device_runs_the_fp32_chains_on_the_matrix_cores():
+    """veda_plan_create probes the device: chains of v_mfma_f32_32x32x2_f32 against the fmaf chains they stand
+    for (rounding, signed zeros, denormal sums and products).  On gfx950 every bit agrees, so plans use the
+    matrix cores; were this to fail on another device or driver, the library would already have switched to
+    the vector units by itself and every bit-exactness test would still hold."""
+    wl = wlm.custom_workload("probe", 1, 64, "f32", (4, 8, 8), False, (1, 2), seed=5, latent_dim=4)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, wlm.tile_shapes(wl), wl.torch_dtype)
+    assert plan.chain_unit() == veda.VEDA_CHAINS_MATRIX
+    plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT, veda.VEDA_CHAINS_VECTOR)
+    assert plan.chain_unit() == veda.VEDA_CHAINS_VECTOR
+    plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT, 0)
+    assert plan.chain_unit() == veda.VEDA_CHAINS_MATRIX
+    with pytest.raises(RuntimeError):
+        plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT, 3)
 
 
 def test_projection_chains_of_odd_length_keep_signed_zeros():
@@ -446,7 +469,8 @@ def test_score_select_in_one_call_long_rows():
     _say(f"[parity] {wl.name} head 0: lists equal on both routes and to the oracle; attention {st}")
 
 
-def test_score_select_in_one_call_ties_nan_and_redone_rows():
+@pytest.mark.parametrize("unit", [0, 2])
+def test_score_select_in_one_call_ties_nan_and_redone_rows(unit):
     # Descriptors doctored against the candidate lists.  Head 0: every key tile is a copy of tile B
     # except 30 of the sampled columns, which are copies of tile A.  For a row that scores A above B
     # the pivot is A's score and only 30 < k candidates exist; for the other rows the pivot is B's
@@ -459,6 +483,8 @@ def test_score_select_in_one_call_ties_nan_and_redone_rows():
     shapes = wlm.tile_shapes(wl)
     q, k, _ = wlm.make_qkv(wl, dev)
     plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    if unit:   # projections and the redone score rows as scalar fmaf chains on the vector units
+        plan.set_option(veda.VEDA_OPT_FP32_CHAIN_UNIT, unit)
     n = plan.tiles[0]
     assert n == 1152 and plan.tiles[1] == n
     kph = wlm.keep_budget(wl, None, shapes)
