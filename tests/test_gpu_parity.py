@@ -315,6 +315,62 @@ def _hand_made_lists(dtype, d, q_gain, tol_gain, check=True, exact_scale=False, 
     return stats
 
 
+def test_a_head_too_long_for_the_step_table():
+    """1,049,600 tokens in one head = 17,600 tiles of 4x4x4, more than the 16,384 the bf16 attention kernel's
+    step table covers: the kernel then merges the kept lists inside its loop.  Hand-made ascending lists (the
+    tile itself, its successor, four drawn ones); sampled query tiles (first, last, ragged ones) against the
+    oracle."""
+    wl = wlm.custom_workload("long_head", 1, 64, "bf16", (41, 160, 160), False, (1, 100), seed=44)
+    dev = torch.device("cuda:0")
+    shapes = wlm.tile_shapes(wl)
+    shape = tuple(int(x) for x in shapes[0])
+    q, k, v = wlm.make_qkv(wl, dev)
+    plan = veda.Plan(wl.batch, wl.heads, wl.head_dim, wl.grid, shapes, wl.torch_dtype)
+    n = plan.tiles[0]
+    assert n == 17600
+    rng = np.random.default_rng(44)
+    ksel = 6
+    sel = np.empty((n, ksel), np.int32)
+    sel[:, 0] = np.arange(n)
+    sel[:, 1] = (np.arange(n) + 1) % n
+    sel[:, 2:] = rng.integers(0, n, (n, ksel - 2))
+    for i in range(n):   # no tile twice in a row: redraw the few duplicates
+        while len(set(sel[i])) < ksel:
+            sel[i, 2:] = rng.integers(0, n, ksel - 2)
+    sel.sort(axis=1)
+    col_idx = torch.as_tensor(sel.reshape(-1)).to(dev)
+    row_ptr = torch.arange(n + 1, dtype=torch.int32, device=dev) * ksel
+    _, vm, _, _ = veda.veda_tile_layout_stats(plan, q, want_tiles=False)
+    vt, _, _ = veda.veda_tile_layout(plan, v, veda.VEDA_CHANNEL_MAJOR, want_mask=False)
+    scale = 1.0 / math.sqrt(wl.head_dim)
+    out = torch.full((1, 1, wl.tokens, wl.head_dim), float("nan"), dtype=wl.torch_dtype, device=dev)
+    out, lse = veda.veda_sparse_attn_fwd(plan, None, None, vt, vm, row_ptr, col_idx, scale, out=out, want_lse=True,
+                                         q_tokens=q, k_tokens=k)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    T, H, W = wl.grid
+    tiles = [0, 1, n // 2, n - 2, n - 1] + [int(x) for x in rng.integers(0, n, 3)]
+    nh, nw = -(-H // shape[1]), -(-W // shape[2])
+    queries = []
+    for i in tiles:
+        tt, th, tw = i // (nh * nw), (i // nw) % nh, i % nw
+        for lt in range(shape[0]):
+            for lh in range(shape[1]):
+                for lw in range(shape[2]):
+                    t, h, w = tt * shape[0] + lt, th * shape[1] + lh, tw * shape[2] + lw
+                    if t < T and h < H and w < W:
+                        queries.append((t * H + h) * W + w)
+    queries = np.asarray(sorted(queries))
+    ref, lse_ref, _ = vo.masked_attention(hz.to_f32_numpy(q[0, 0]), hz.to_f32_numpy(k[0, 0]), hz.to_f32_numpy(v[0, 0]),
+                                          wl.grid, shape, sel, scale, queries, want_stats=True)
+    got = hz.to_f32_numpy(out[0, 0][torch.as_tensor(queries, device=dev)]).astype(np.float64)
+    err = np.abs(got - ref)
+    lerr = np.abs(lse[0, 0][torch.as_tensor(queries, device=dev)].cpu().numpy().astype(np.float64) - lse_ref)
+    _say(f"[parity] {wl.name}: {len(queries)} sampled queries of {n} tiles: max_abs {err.max():.2e} mean_abs {err.mean():.2e} "
+         f"lse {lerr.max():.2e}")
+    assert err.max() <= hz.BF16_MAX_ABS and err.mean() <= hz.BF16_MEAN_ABS and lerr.max() <= 2e-2
+
+
 def test_maximum_head_count():
     # 128 heads (the library's limit) on a small ragged grid: per-head tables, the die-aware work
     # split and the 64-tile projection blocks all see many short heads
