@@ -12,8 +12,9 @@
  *  - Arguments are checked on the host before anything is launched; a failed check returns
  *    an error code and launches nothing.  HIP launch failures map to VEDA_ERR_HIP.
  *  - No data-dependent scheduling of arithmetic and no floating-point atomics: equal inputs give
- *    equal bytes.  (The only atomics are the integer adds of veda_tile_recall's hit counters,
- *    whose sum does not depend on their order.)
+ *    equal bytes.  (The only atomics are integer ones whose result does not depend on their
+ *    order: the adds of veda_tile_recall's hit counters, and the bit-sets in LDS with which the
+ *    bf16 attention kernel turns a kept list into a bitmap.)
  *  - Tokens are the raster flattening n = (t*H + h)*W + w of a latent grid (T,H,W)
  *    (Sec. 3.1).  A head's tile shape pi = (p_t,p_h,p_w) with p_t*p_h*p_w = B (Eq. 7)
  *    partitions the grid, each axis padded up to a multiple of the tile extent.  Tile i and

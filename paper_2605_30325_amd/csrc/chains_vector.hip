@@ -174,9 +174,9 @@ veda_status probe_chain_unit(int device, int* unit) {
         VEDA_HIP_TRY(hipMalloc((void**)&d_bad, 128 * sizeof(int32_t)));
         int total = 0;
         hipError_t e = hipSuccess;
-        for (uint32_t round = 0; round < 8 && e == hipSuccess; ++round) {
+        for (uint32_t pass = 0; pass < 8 && e == hipSuccess; ++pass) {
             int32_t bad[128];
-            hipLaunchKernelGGL(chain_probe_kernel, dim3(1), dim3(128), 0, 0, d_bad, 0x9e3779b9u * (round + 1), (int)(2 * round));
+            hipLaunchKernelGGL(chain_probe_kernel, dim3(1), dim3(128), 0, 0, d_bad, 0x9e3779b9u * (pass + 1), (int)(2 * pass));
             e = hipGetLastError();
             if (e == hipSuccess) e = hipMemcpy(bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost);
             if (e == hipSuccess)
