@@ -887,6 +887,30 @@ def test_128_token_tiles_at_full_size(name):
         assert torch.isfinite(run.out[0, h].float()).all(), h
 
 
+@pytest.mark.parametrize("tile_tokens", [64, 128])
+def test_list_walk_and_step_table_give_the_same_bits_at_full_size(tile_tokens):
+    """wan14b_720p at its launch size: stage 3 writes ascending rows, so the attention kernel visits the key
+    tiles in the same order whether it lays its steps out in LDS first or merges the lists inside its loop
+    (VEDA_OPT_ATTN_LIST_WALK): every output bit agrees, from tiled K and Q and from token order."""
+    wl = wlm.WORKLOADS["wan14b_720p"]
+    shapes = wlm.tile_shapes(wl) * (np.asarray([2, 1, 1], np.int32) if tile_tokens == 128 else 1)
+    run = hz.run_gpu_path(wl, k_per_head=wlm.keep_budget(wl, None, shapes), shapes=shapes, tile_tokens=tile_tokens)
+    b, plan = run.bufs, run.plan
+    args = (b["vt"], b["vm"], b["rp"], b["ci"], run.softmax_scale)
+    outs = []
+    for walk in (0, 1):
+        plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, walk)
+        o1, l1 = veda.veda_sparse_attn_fwd(plan, b["qt"], b["kt"], *args, want_lse=True)
+        o2, l2 = veda.veda_sparse_attn_fwd(plan, None, None, *args, want_lse=True, q_tokens=run.q, k_tokens=run.k)
+        torch.cuda.synchronize()
+        outs.append((o1, l1, o2, l2))
+    plan.set_option(veda.VEDA_OPT_ATTN_LIST_WALK, 0)
+    for x, y in zip(outs[0], outs[1]):
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x, y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+    assert torch.equal(outs[0][0].view(torch.int16), run.out.view(torch.int16))
+    assert torch.equal(outs[0][0].view(torch.int16), outs[0][2].view(torch.int16))
+
+
 def test_rows_three_times_longer_than_any_named_workload():
     """783,360 tokens in one head (12,240 tiles per score row): the whole path against the oracle at a 2 %
     budget (stages 2+3 in one call take the candidate route), then the lists at a 5 % budget (k = 612, where
