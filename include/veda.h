@@ -14,7 +14,7 @@
  *  - No data-dependent scheduling of arithmetic and no floating-point atomics: equal inputs give
  *    equal bytes.  (The only atomics are integer ones whose result does not depend on their
  *    order: the adds of veda_tile_recall's hit counters, and the bit-sets in LDS with which the
- *    bf16 attention kernel turns a kept list into a bitmap.)
+ *    attention kernels turn a kept list into a bitmap.)
  *  - Tokens are the raster flattening n = (t*H + h)*W + w of a latent grid (T,H,W)
  *    (Sec. 3.1).  A head's tile shape pi = (p_t,p_h,p_w) with p_t*p_h*p_w = B (Eq. 7)
  *    partitions the grid, each axis padded up to a multiple of the tile extent.  Tile i and
@@ -99,7 +99,7 @@ void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
 /* Options of a plan; they take effect for the stage calls made after the setter returns.
  * VEDA_OPT_EXACT_LOGIT_SCALE (0 = off, the default; 1 = on), bf16 stage 4 (Eq. 2): see
  * veda_sparse_attn_fwd.
- * VEDA_OPT_ATTN_LIST_WALK (0 = off, the default; 1 = on), bf16 stage 4 (Sec. 4.3): the kernel
+ * VEDA_OPT_ATTN_LIST_WALK (0 = off, the default; 1 = on), stage 4 (Sec. 4.3): the kernel
  * normally works out, before its main loop, the order in which a workgroup visits the key tiles
  * its query tiles keep (ascending, whatever the order inside the lists) into a table in LDS;
  * with this option it merges the lists as it goes instead, reading them entry by entry (then

@@ -60,7 +60,7 @@ static veda_status sparse_attn(const veda_plan* pl, const void* q_tiled, const v
         return launch_sparse_attn_bf16_pair(ip, a, pl->inner != nullptr, pl->exact_logit_scale, pl->attn_list_walk, s);
     }
     a.xcd_cum = pl->d_xcd_cum_pair;
-    return launch_sparse_attn_f32(pl, a, s);
+    return launch_sparse_attn_f32(pl, a, pl->attn_list_walk, s);
 }
 
 }  // namespace veda

@@ -153,6 +153,6 @@ veda_status launch_sparse_attn_bf16_pair(const veda_plan* pl, const AttnArgs& a,
                                          hipStream_t s);
 
 // The fp32 kernel (attn_f32.hip): same work items (a.xcd_cum must be the plan's pair table), tiled Q, K, V only.
-veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, hipStream_t s);
+veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, bool walk, hipStream_t s);
 
 }  // namespace veda

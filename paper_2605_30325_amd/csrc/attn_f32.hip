@@ -18,6 +18,7 @@
 // the direct loads.  Plain online softmax (reference = running row maximum), exp2 with log2(e)
 // folded into Q in fp32.
 #include "attn_common.h"
+#include "attn_union.h"
 
 namespace veda {
 
@@ -25,7 +26,11 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef const __attribute__((address_space(3))) f32x4* lds_f32x4_ptr;
 __device__ __forceinline__ f32x4 lds_read_f32x4(uint32_t addr) { return *(lds_f32x4_ptr)(uintptr_t)addr; }
 
-template <int D>
+constexpr int kF32Chunk = 256;   // step-table entries filled at a time
+
+// kTable: the steps come from the table in LDS (attn_union.h), as in the bf16 kernel; otherwise the two
+// lists are merged inside the loop (heads above 16384 tiles, VEDA_OPT_ATTN_LIST_WALK).
+template <int D, bool kTable>
 __global__ __launch_bounds__(256, 1) void sparse_attn_f32_kernel(AttnArgs a) {
     constexpr int kKPitch = D * 4;               // bytes of one K row
     constexpr int kKBytes = kTile * kKPitch;     // K tile
@@ -116,13 +121,42 @@ __global__ __launch_bounds__(256, 1) void sparse_attn_f32_kernel(AttnArgs a) {
     const uint32_t k_row0 = smem_base + idx * kKPitch;               // key block 0: row idx (block 1: + 32 rows)
     const uint32_t v_row0 = smem_base + kKBytes + idx * kVPitch;     // channel block 0: row idx (block nb: + 32 nb rows)
 
-    // Merged walk over the two kept lists (scalar unit, 32-bit integers; see the bf16 kernel).
+    // The steps: the union of the two kept lists.  Table mode: laid out in LDS before the loop; walk mode:
+    // merged with scalar loads as the loop goes (32-bit integers on the scalar unit; see the bf16 kernel).
     constexpr int kEnd = 0x7fffffff;
     int ia = 0, ib = 0;
-    int rawA = colsA[0], rawB = colsB[0];
-    int okA = nA > 0 ? 1 : 0, okB = nB > 0 ? 1 : 0;
+    int rawA = 0, rawB = 0, okA = 0, okB = 0;
     struct Step { int j, fl; uint64_t vm; };
+    typedef UnionLds<2, kF32Chunk> Table;
+    Table& u = *reinterpret_cast<Table*>(smem + 2 * kSlot);
+    const uint32_t tab_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)&u.tab[0];
+    const uint64_t* vmask_g = a.valid_mask + hg.tile_off;
+    const int32_t* n0s_g = a.tile_n0 + hg.tile_off;
+    i32x4 raw_next = {0, 0, 0, 0};
+    int s_read = 0, s_done = 0, total = 0;
+    if constexpr (kTable) {
+        const int32_t* lists[2] = {a.col_idx + begA, a.col_idx + begB};
+        const int counts[2] = {nA, nB};
+        total = union_build<2, 256, kF32Chunk>(u, lists, counts, hg.n_tiles, tid);
+        union_fill<2, 256, kF32Chunk, false>(u, 0, total, hg.n_tiles, vmask_g, n0s_g, tid);
+        union_fill<2, 256, kF32Chunk, false>(u, kF32Chunk, total, hg.n_tiles, vmask_g, n0s_g, tid);
+        __syncthreads();
+        raw_next = union_read<kF32Chunk>(tab_lds, 0);
+        s_read = 1;
+    } else {
+        rawA = colsA[0];
+        rawB = colsB[0];
+        okA = nA > 0 ? 1 : 0;
+        okB = nB > 0 ? 1 : 0;
+    }
     auto next_step = [&](Step& e) __attribute__((always_inline)) {
+        if constexpr (kTable) {
+            const UnionStep t = union_step(raw_next);
+            e.j = t.j; e.fl = t.fl; e.vm = t.vm;
+            raw_next = union_read<kF32Chunk>(tab_lds, s_read);
+            ++s_read;
+            return;
+        }
         const int headA = okA ? rawA : kEnd, headB = okB ? rawB : kEnd;
         const int jm = headA < headB ? headA : headB;
         const int live = jm != kEnd ? 1 : 0;
@@ -217,6 +251,11 @@ __global__ __launch_bounds__(256, 1) void sparse_attn_f32_kernel(AttnArgs a) {
         e1 = e2;
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads of the next tiles have landed
         __syncthreads();
+        if constexpr (kTable) {   // the table's other half has been left behind: refill it
+            ++s_done;
+            if ((s_done & (kF32Chunk - 1)) == 0)
+                union_fill<2, 256, kF32Chunk, false>(u, s_done + kF32Chunk, total, hg.n_tiles, vmask_g, n0s_g, tid);
+        }
     }
 
     // Normalise, transpose through LDS ([2 tiles][64 rows][D] fp32) and scatter the real rows.
@@ -255,17 +294,26 @@ __global__ __launch_bounds__(256, 1) void sparse_attn_f32_kernel(AttnArgs a) {
     }
 }
 
-veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, hipStream_t s) {
+veda_status launch_sparse_attn_f32(const veda_plan* pl, const AttnArgs& a, bool walk, hipStream_t s) {
     const int d = pl->prob.head_dim;
     dim3 grid((unsigned)(kXcd * pl->xcd_max_pairs), (unsigned)pl->prob.batch), block(256);
-    const size_t smem = (size_t)2 * 2 * kTile * d * 4;   // two slots of (K tile + V^T tile)
+    bool table = !walk;   // the step table's bitmaps cover 16384 tiles per head
+    for (const HeadGeom& g : pl->heads) table = table && g.n_tiles <= kUnionMaxTiles;
+    // two slots of (K tile + V^T tile), then the step table
+    const size_t smem = (size_t)2 * 2 * kTile * d * 4 + (table ? sizeof(UnionLds<2, kF32Chunk>) : 0);
+#define VEDA_LAUNCH_F32(DD, TT)                                                                          \
+    do {                                                                                                 \
+        auto kern = sparse_attn_f32_kernel<DD, TT>;                                                      \
+        if (smem > 64 * 1024)                                                                            \
+            VEDA_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)); \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, a);                                               \
+    } while (0)
     if (d == 128) {
-        VEDA_HIP_TRY(hipFuncSetAttribute((const void*)sparse_attn_f32_kernel<128>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-        hipLaunchKernelGGL(sparse_attn_f32_kernel<128>, grid, block, smem, s, a);
+        if (table) VEDA_LAUNCH_F32(128, true); else VEDA_LAUNCH_F32(128, false);
     } else {
-        hipLaunchKernelGGL(sparse_attn_f32_kernel<64>, grid, block, smem, s, a);
+        if (table) VEDA_LAUNCH_F32(64, true); else VEDA_LAUNCH_F32(64, false);
     }
+#undef VEDA_LAUNCH_F32
     return launch_status("sparse_attn_f32_kernel");
 }
 

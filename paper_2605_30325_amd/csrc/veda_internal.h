@@ -62,7 +62,7 @@ struct veda_plan {
     int64_t score_blocks = 0;
     int device = -1;
     bool exact_logit_scale = false;     // VEDA_OPT_EXACT_LOGIT_SCALE (bf16 attention kernel)
-    bool attn_list_walk = false;        // VEDA_OPT_ATTN_LIST_WALK (bf16 attention kernel)
+    bool attn_list_walk = false;        // VEDA_OPT_ATTN_LIST_WALK (attention kernels)
     // Where the fixed-order fp32 chains of stage 2 run: chain_probe is what probe_chain_unit found on
     // this plan's device, chain_option what VEDA_OPT_FP32_CHAIN_UNIT asks for (0 = as probed).
     int chain_probe = VEDA_CHAINS_MATRIX, chain_option = 0;

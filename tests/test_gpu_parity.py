@@ -219,11 +219,11 @@ def test_row_stochastic_weights_on_gpu():
 
 
 @pytest.mark.parametrize("dtype,d,walk", [("bf16", 128, False), ("bf16", 64, False), ("f32", 64, False),
-                                          ("bf16", 128, True), ("bf16", 64, True)])
+                                          ("bf16", 128, True), ("bf16", 64, True), ("f32", 64, True)])
 def test_attention_on_hand_made_lists(dtype, d, walk):
     # Stage 4 alone on kept lists that stage 3 would never write: unsorted, neighbours with
     # identical / disjoint / partly shared lists.  The grid gives every head an odd tile count
-    # (the last query tile has no neighbour) and ragged tiles on every axis.  walk: the bf16 kernel
+    # (the last query tile has no neighbour) and ragged tiles on every axis.  walk: the kernel
     # merging the lists inside its loop (VEDA_OPT_ATTN_LIST_WALK) instead of from its step table.
     _hand_made_lists(dtype, d, 1.0, 1.0, walk=walk)
 
