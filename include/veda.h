@@ -92,7 +92,11 @@ typedef struct {
 /* ---- plan: host-side geometry of a problem --------------------------------------------- */
 
 /* Validates the problem, derives each head's tile grid and offsets, uploads the per-head
- * table to the current device.  *out is written only on VEDA_OK. */
+ * table to the current device.  The first plan made on a device also resolves the address of
+ * the no-allocation entry point's scratch array there and measures where stage 2's fp32 chains
+ * may run (VEDA_OPT_FP32_CHAIN_UNIT): a few small kernel launches on the default stream and one
+ * copy back, synchronous.  Not to be called under stream capture.  *out is written only on
+ * VEDA_OK. */
 veda_status veda_plan_create(const veda_problem* problem, veda_plan** out);
 void veda_plan_destroy(veda_plan* plan); /* NULL is allowed */
 
